@@ -1,0 +1,151 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched plan-search dynamic program on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic search
+instances that already live in HBM: galv_dp_solve_batched (preparation, layer 0,
+the L-1 layer sweeps, final minimum) followed by galv_dp_backtrack.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
+
+Prints ONE JSON line.  `value` is DP cell-updates/s with the metric's nominal
+count sum_b L * E_b * S^2 per batch; searches/s and the exact candidate rate are
+reported beside it.  `roofline` is for the layer-sweep kernel (the only kernel
+that matters: > 99 % of the time): exact min-plus candidates per launch times
+the 2 VALU lane-operations each one needs (one 64-bit add, one 64-bit min),
+divided by the average launch duration measured with events on the launch
+stream, against the chip's VALU issue peak of 256 CUs x 64 lanes x 2.4 GHz =
+39.3 T lane-ops/s.  `cpu_baseline` times the serial CPU oracle (test
+infrastructure, never tuned) on a sample of instances of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+VALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12      # 39.3
+HBM_PEAK_GBS = 8000.0
+OPS_PER_CANDIDATE = 2                              # v_add_f64 + v_min_f64
+BYTES_PER_STATE = 20                               # 8 B read + 8 B write of the cost row, 4 B back-pointer
+
+
+def cpu_baseline(w, seconds_hint=20.0):
+    """Oracle wall time on a bounded sample of the workload's instances."""
+    import oracle
+    oracle.build()
+    threads = max(1, min(8, os.cpu_count() or 1))
+    # spread the sample over the batch (budgets differ across instances)
+    ids = sorted({int(round(i * (w.B - 1) / max(1, threads - 1))) for i in range(threads)})
+    per_inst = [w.L * int(w.budget[b]) * w.S * w.S for b in ids]
+    # keep the sample near the time hint assuming ~0.7e9 updates/s per core
+    while len(ids) > 1 and max(per_inst) / 0.7e9 > seconds_hint:
+        drop = per_inst.index(max(per_inst))
+        ids.pop(drop); per_inst.pop(drop)
+    t0 = time.perf_counter()
+    oracle.solve_workload(w, ids, threads=len(ids))
+    dt = time.perf_counter() - t0
+    return {"value": sum(per_inst) / dt, "unit": "cell-updates/s", "cores": len(ids),
+            "kind": "oracle", "seconds": round(dt, 3),
+            "sample": f"{len(ids)} of {w.B} instances of '{w.name}' (ids {ids}), one per thread, "
+                      f"full L and budget each"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=3, help="workload index 0..4 (default 3)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--force-int64", action="store_true", help="time the general integer kernels")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; instances are independent, so more GPUs "
+              "would just split the batch (no multi-GPU path is part of it). Use --gpus 1.",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2211_13878_amd import binding, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    w = workloads.config(args.config)
+    flags = binding.GALV_DP_FORCE_INT64 if args.force_int64 else 0
+    sol = binding.Solver(w.B, w.L, w.S, w.E_max, w.nR, flags)
+    dev = binding.upload(w)
+    torch.cuda.synchronize()
+
+    def step():
+        sol.solve(*dev)
+        sol.backtrack()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # Events sit on torch's current stream, which is the stream the binding hands
+    # to the library, so they bracket exactly the library's launches.
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record()
+        sol.solve(*dev)
+        b.record()
+        sol.backtrack()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    solve_ms = sorted(a.elapsed_time(b) for a, b in ev)
+    status = sol.status().cpu().numpy()
+    cost = sol.best_cost.cpu().numpy()
+
+    ms_per_step = wall * 1e3 / args.steps
+    nominal = w.nominal_cell_updates()
+    exact = w.exact_candidates()
+    states = w.n_states()
+    n_launch = max(1, w.L - 1)
+    sweep_ms = sum(solve_ms) / len(solve_ms) / n_launch      # average sweep launch (upper bound:
+    #                                                           includes prep/init/final, < 1 %)
+    ops = OPS_PER_CANDIDATE if not args.force_int64 else 6
+    achieved = exact / n_launch * ops / (sweep_ms * 1e-3) / 1e12
+    hbm_gbs = states / w.L * BYTES_PER_STATE / (sweep_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "dp_cell_updates_per_sec",
+        "value": nominal / (ms_per_step * 1e-3),
+        "unit": "cell-updates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int64" if args.force_int64 else "f64 (exact integer keys; int64 in, int64 out)",
+        "data": "synthetic",
+        "config": {"workload": f"config {args.config} '{w.name}': B={w.B} L={w.L} S={w.S} "
+                               f"E_max={w.E_max} budgets {int(w.budget.min())}..{int(w.budget.max())}",
+                   "cell_updates_per_batch": nominal, "exact_candidates_per_batch": exact,
+                   "table_states_per_batch": states},
+        "searches_per_sec": w.B / (ms_per_step * 1e-3),
+        "exact_candidates_per_sec": exact / (ms_per_step * 1e-3),
+        "solve_ms_median": solve_ms[len(solve_ms) // 2],
+        "instances_fast_path": int((status == binding.GALV_INSTANCE_OK_FAST).sum()),
+        "instances_feasible": int((cost < binding.GALV_INF).sum()),
+        "roofline": {"bound": "alu", "kernel": "sweep_kernel", "achieved": achieved,
+                     "peak": VALU_PEAK_TLANEOPS, "unit": "Tlane-op/s",
+                     "frac": achieved / VALU_PEAK_TLANEOPS, "traffic": None,
+                     "launch_ms": sweep_ms, "lane_ops_per_candidate": ops,
+                     "hbm": {"achieved": hbm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "frac": hbm_gbs / HBM_PEAK_GBS, "bytes_per_state": BYTES_PER_STATE}},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,145 @@
+/*
+ * galv_dp.h — C ABI of the batched plan-search dynamic program for AMD MI355X (gfx950).
+ *
+ * The library solves, for many independent search instances at once, the
+ * layer-by-layer dynamic program that picks one parallelism strategy per model
+ * layer under a device memory budget (paper section 3.3, "Dynamic Programming
+ * Search", Eq. 1; it is the routine Algorithm 1 calls once per batch size,
+ * pipeline degree and stage).  For an instance with L layers, S candidate
+ * strategies and budget E it finds the plan p in {0..S-1}^L with
+ * sum_l m(l, p_l) <= E that minimises
+ *
+ *     sum_l c(l, p_l)  +  sum_{l >= 1} R_{r_idx[l]}(p_{l-1}, p_l)
+ *
+ * through the recurrence  C[l][e][s] = c(l,s) + min_{s'} ( C[l-1][e - m(l,s)][s'] + R(s', s) ),
+ * C[0][e][s] = c(0,s) when m(0,s) <= e, followed by an argmin walk over stored
+ * back-pointers.  Costs are exact 64-bit integers; every minimum is broken
+ * towards the lowest index; "infinity" (no admissible plan: the paper's
+ * Out-Of-Memory outcome) is GALV_INF.
+ *
+ * Conventions
+ *  - Pointers named *_dev are DEVICE pointers (HBM of the current HIP device);
+ *    everything else is host memory.  `stream` is a hipStream_t passed as void*
+ *    (NULL = the default stream).
+ *  - The caller owns all device buffers, including the workspace, and keeps the
+ *    inputs alive and unchanged until the stream has passed the calls that read
+ *    them (m_dev and budget_dev until the last backtrack / export of that solve).
+ *  - solve / backtrack / export only enqueue work on `stream`; they never
+ *    synchronise and never allocate.  galv_dp_create enqueues a one-time
+ *    workspace initialisation on the default stream and waits for it.
+ *  - Errors in host-visible arguments are returned as codes (never exceptions,
+ *    never abort); galv_dp_last_error() gives a thread-local message.
+ *  - Input VALUES live on the device and cannot be checked synchronously: a
+ *    per-instance device status (galv_dp_get_status) reports them instead.
+ *    An instance with invalid values yields GALV_INF / -1 like an infeasible one.
+ *  - Preconditions on values: c >= 0, R >= 0, m >= 0, 0 <= budget <= max_budget,
+ *    0 <= r_idx < n_transition, and  sum_l max_s c(l,s) + sum_{l>=1} max R_{r_idx[l]} < 2^62.
+ *  - One handle serves one solve at a time: concurrent calls on one handle race.
+ */
+#ifndef GALV_DP_H
+#define GALV_DP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct galv_dp galv_dp_t; /* opaque handle, host memory, owned by the library */
+
+#define GALV_INF ((int64_t)1 << 62) /* "infinity": infeasible / Out-Of-Memory */
+
+typedef enum {
+    GALV_OK = 0,
+    GALV_ERR_INVALID_ARG = 1, /* NULL pointer, size out of range, bad instance index     */
+    GALV_ERR_WORKSPACE = 2,   /* workspace NULL, misaligned (256 B) or too small         */
+    GALV_ERR_RANGE = 3,       /* sizes whose tables cannot be indexed (overflow)         */
+    GALV_ERR_HIP = 4,         /* a HIP runtime call failed; see galv_dp_last_error()     */
+    GALV_ERR_STATE = 5        /* call order: backtrack / export / status before a solve  */
+} galv_status_t;
+
+/* Problem shape, common to all instances of a batch. */
+typedef struct {
+    int32_t n_instances;  /* B  >= 1 */
+    int32_t n_layers;     /* L  >= 1 */
+    int32_t n_strategies; /* S  in [1, 1024] */
+    int32_t max_budget;   /* E_max >= 0: tables have E_max + 1 budget columns            */
+    int32_t n_transition; /* nR >= 1 transition matrices per instance                    */
+    uint32_t flags;       /* GALV_DP_* below, 0 for defaults                             */
+} galv_dp_desc_t;
+
+/* flags */
+#define GALV_DP_FORCE_INT64 1u /* always use the general 64-bit integer kernels, even when
+                                  an instance's values would allow the faster exact path */
+
+/* Per-instance status codes written by solve (see galv_dp_get_status). */
+#define GALV_INSTANCE_OK_FAST 0   /* solved by the exact floating-key kernels          */
+#define GALV_INSTANCE_OK_INT64 1  /* solved by the general 64-bit integer kernels      */
+#define GALV_INSTANCE_BAD_VALUE (-1) /* a value violates the preconditions above       */
+
+/*
+ * Bytes of device workspace a handle for `desc` needs (rolling cost rows,
+ * back-pointers for layers 1..L-1, packed transition tables, per-instance
+ * state): roughly B * S * (E_max + 1) * (4 * (L - 1) + 32) bytes.
+ */
+galv_status_t galv_dp_workspace_bytes(const galv_dp_desc_t *desc, size_t *bytes);
+
+/*
+ * Create a handle over caller-owned workspace (256-byte aligned device memory
+ * of at least galv_dp_workspace_bytes).  The handle keeps the pointer; the
+ * workspace must outlive it.  The device that is current at this call is the
+ * one every later call on the handle must run on.
+ */
+galv_status_t galv_dp_create(const galv_dp_desc_t *desc, void *workspace_dev,
+                             size_t workspace_bytes, galv_dp_t **out);
+
+/*
+ * Run the recurrence of Eq. 1 for all B instances (layers 0..L-1, every budget
+ * column 0..budget[b]) and the final minimum at e = budget[b].
+ *   c_dev      [B][L][S]      int64  execution time c(l, s)
+ *   m_dev      [B][L][S]      int32  memory units m(l, s); m > budget[b] => (l, s) unusable
+ *   R_dev      [B][nR][S][S]  int64  R[k][s_prev][s_cur], cost of changing layout between
+ *                                    a layer on s_prev and the next layer on s_cur
+ *   r_idx_dev  [B][L]         int32  matrix k used between layer l-1 and l (entry 0 unused);
+ *                                    NULL => matrix 0 everywhere
+ *   budget_dev [B]            int32  budget of each instance
+ *   best_cost_dev [B]  out    int64  optimum, GALV_INF when no plan fits
+ *   best_last_dev [B]  out    int32  strategy of layer L-1 in the optimal plan, -1 if none
+ */
+galv_status_t galv_dp_solve_batched(galv_dp_t *h, const int64_t *c_dev, const int32_t *m_dev,
+                                    const int64_t *R_dev, const int32_t *r_idx_dev,
+                                    const int32_t *budget_dev, int64_t *best_cost_dev,
+                                    int32_t *best_last_dev, void *stream);
+
+/*
+ * Recover the optimal plan of every instance of the last solve by walking the
+ * back-pointers from (L-1, budget[b], best_last[b]) to layer 0.
+ *   plan_dev [B][L] out int32  strategy index per layer; all -1 when no plan fits.
+ * Must be enqueued on the same stream as (or ordered after) the solve.
+ */
+galv_status_t galv_dp_backtrack(galv_dp_t *h, int32_t *plan_dev, void *stream);
+
+/*
+ * Test / debug: write one instance's tables of the last solve in canonical
+ * order, as the recurrence defines them.
+ *   C_last_dev [E_max+1][S]      int64  C[L-1][e][s]; GALV_INF when unreachable or e > budget
+ *   bp_dev     [L][E_max+1][S]   int32  minimising s' of cell (l, e, s); -1 for layer 0,
+ *                                       unreachable cells and e > budget.  May be NULL.
+ */
+galv_status_t galv_dp_export_tables(galv_dp_t *h, int32_t instance, int64_t *C_last_dev,
+                                    int32_t *bp_dev, void *stream);
+
+/* Copy the per-instance status codes of the last solve: status_dev [B] int32. */
+galv_status_t galv_dp_get_status(galv_dp_t *h, int32_t *status_dev, void *stream);
+
+/* Free the handle (host memory only; the workspace stays the caller's). NULL is allowed. */
+galv_status_t galv_dp_destroy(galv_dp_t *h);
+
+/* Message of the last error on this thread ("" if none). Never NULL. */
+const char *galv_dp_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GALV_DP_H */

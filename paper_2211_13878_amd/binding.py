@@ -1,0 +1,198 @@
+"""Thin ctypes binding over libgalvdp.so (the C ABI declared in include/galv_dp.h).
+
+Argument marshalling only: every step of the search runs in the library's HIP
+kernels.  PyTorch is used for device memory (tensors own every buffer) and for
+the current stream.  There is no CPU fallback: a missing library raises.
+
+The module-level functions carry the C names and take device tensors; `Solver`
+bundles a handle with the workspace tensor it lives in.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgalvdp.so")
+
+GALV_INF = 1 << 62
+GALV_OK = 0
+GALV_ERR_INVALID_ARG, GALV_ERR_WORKSPACE, GALV_ERR_RANGE, GALV_ERR_HIP, GALV_ERR_STATE = 1, 2, 3, 4, 5
+GALV_DP_FORCE_INT64 = 1
+GALV_INSTANCE_OK_FAST, GALV_INSTANCE_OK_INT64, GALV_INSTANCE_BAD_VALUE = 0, 1, -1
+
+EXPORTS = ("galv_dp_workspace_bytes", "galv_dp_create", "galv_dp_solve_batched",
+           "galv_dp_backtrack", "galv_dp_export_tables", "galv_dp_get_status",
+           "galv_dp_destroy", "galv_dp_last_error")
+
+
+class GalvError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"galv_dp error {code}: {message}")
+        self.code = code
+
+
+class Desc(ctypes.Structure):
+    _fields_ = [("n_instances", ctypes.c_int32), ("n_layers", ctypes.c_int32),
+                ("n_strategies", ctypes.c_int32), ("max_budget", ctypes.c_int32),
+                ("n_transition", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libgalvdp.so built in-tree; fail loudly when it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2211_13878_amd.build` "
+                "(there is no CPU fallback)")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i32 = ctypes.c_void_p, ctypes.c_int32
+        lib.galv_dp_workspace_bytes.argtypes = [ctypes.POINTER(Desc), ctypes.POINTER(ctypes.c_size_t)]
+        lib.galv_dp_create.argtypes = [ctypes.POINTER(Desc), vp, ctypes.c_size_t, ctypes.POINTER(vp)]
+        lib.galv_dp_solve_batched.argtypes = [vp] * 9
+        lib.galv_dp_backtrack.argtypes = [vp, vp, vp]
+        lib.galv_dp_export_tables.argtypes = [vp, i32, vp, vp, vp]
+        lib.galv_dp_get_status.argtypes = [vp, vp, vp]
+        lib.galv_dp_destroy.argtypes = [vp]
+        for name in EXPORTS[:-1]:
+            getattr(lib, name).restype = ctypes.c_int
+        lib.galv_dp_last_error.restype = ctypes.c_char_p
+        _lib = lib
+    return _lib
+
+
+def galv_dp_last_error() -> str:
+    return load_library().galv_dp_last_error().decode()
+
+
+def _check(code: int):
+    if code != GALV_OK:
+        raise GalvError(code, galv_dp_last_error())
+
+
+def _dev_ptr(t, dtype, shape=None, allow_none=False):
+    if t is None:
+        if allow_none:
+            return None
+        raise GalvError(GALV_ERR_INVALID_ARG, "a required tensor is None")
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise GalvError(GALV_ERR_INVALID_ARG, f"expected a contiguous device tensor of {dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise GalvError(GALV_ERR_INVALID_ARG, f"expected shape {tuple(shape)}, got {tuple(t.shape)}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def make_desc(B, L, S, E_max, nR=1, flags=0) -> Desc:
+    return Desc(B, L, S, E_max, nR, flags)
+
+
+def galv_dp_workspace_bytes(desc: Desc) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load_library().galv_dp_workspace_bytes(ctypes.byref(desc), ctypes.byref(n)))
+    return n.value
+
+
+def galv_dp_create(desc: Desc, workspace: torch.Tensor) -> ctypes.c_void_p:
+    h = ctypes.c_void_p(None)
+    ws = _dev_ptr(workspace, torch.uint8)
+    _check(load_library().galv_dp_create(ctypes.byref(desc), ws, workspace.numel(), ctypes.byref(h)))
+    return h
+
+
+def galv_dp_solve_batched(h, c, m, R, r_idx, budget, best_cost, best_last, stream=None):
+    _check(load_library().galv_dp_solve_batched(
+        h, _dev_ptr(c, torch.int64), _dev_ptr(m, torch.int32), _dev_ptr(R, torch.int64),
+        _dev_ptr(r_idx, torch.int32, allow_none=True), _dev_ptr(budget, torch.int32),
+        _dev_ptr(best_cost, torch.int64), _dev_ptr(best_last, torch.int32), _stream_ptr(stream)))
+
+
+def galv_dp_backtrack(h, plan, stream=None):
+    _check(load_library().galv_dp_backtrack(h, _dev_ptr(plan, torch.int32), _stream_ptr(stream)))
+
+
+def galv_dp_export_tables(h, instance, C_last, bp, stream=None):
+    _check(load_library().galv_dp_export_tables(
+        h, int(instance), _dev_ptr(C_last, torch.int64),
+        _dev_ptr(bp, torch.int32, allow_none=True), _stream_ptr(stream)))
+
+
+def galv_dp_get_status(h, status, stream=None):
+    _check(load_library().galv_dp_get_status(h, _dev_ptr(status, torch.int32), _stream_ptr(stream)))
+
+
+def galv_dp_destroy(h):
+    _check(load_library().galv_dp_destroy(h))
+
+
+class Solver:
+    """A handle plus the device workspace it was created over."""
+
+    def __init__(self, B, L, S, E_max, nR=1, flags=0, device="cuda:0"):
+        self.device = torch.device(device)
+        self.B, self.L, self.S, self.E_max, self.nR = B, L, S, E_max, nR
+        self.desc = make_desc(B, L, S, E_max, nR, flags)
+        self.workspace_bytes = galv_dp_workspace_bytes(self.desc)
+        with torch.cuda.device(self.device):
+            self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=self.device)
+            self.handle = galv_dp_create(self.desc, self.workspace)
+        self.best_cost = torch.empty(B, dtype=torch.int64, device=self.device)
+        self.best_last = torch.empty(B, dtype=torch.int32, device=self.device)
+        self.plan = torch.empty((B, L), dtype=torch.int32, device=self.device)
+        self._inputs = None
+
+    def solve(self, c, m, R, r_idx, budget, stream=None):
+        """Enqueue the sweep; returns (best_cost[B], best_last[B]) device tensors."""
+        B, L, S, nR = self.B, self.L, self.S, self.nR
+        _dev_ptr(c, torch.int64, (B, L, S)); _dev_ptr(m, torch.int32, (B, L, S))
+        _dev_ptr(R, torch.int64, (B, nR, S, S)); _dev_ptr(budget, torch.int32, (B,))
+        if r_idx is not None:
+            _dev_ptr(r_idx, torch.int32, (B, L))
+        self._inputs = (c, m, R, r_idx, budget)      # keep alive for backtrack / export
+        galv_dp_solve_batched(self.handle, c, m, R, r_idx, budget, self.best_cost,
+                              self.best_last, stream)
+        return self.best_cost, self.best_last
+
+    def backtrack(self, stream=None):
+        galv_dp_backtrack(self.handle, self.plan, stream)
+        return self.plan
+
+    def export_tables(self, instance, want_bp=True, stream=None):
+        C_last = torch.empty((self.E_max + 1, self.S), dtype=torch.int64, device=self.device)
+        bp = (torch.empty((self.L, self.E_max + 1, self.S), dtype=torch.int32, device=self.device)
+              if want_bp else None)
+        galv_dp_export_tables(self.handle, instance, C_last, bp, stream)
+        return C_last, bp
+
+    def status(self, stream=None):
+        st = torch.empty(self.B, dtype=torch.int32, device=self.device)
+        galv_dp_get_status(self.handle, st, stream)
+        return st
+
+    def close(self):
+        if self.handle is not None:
+            galv_dp_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def upload(w, device="cuda:0"):
+    """Copy a workloads.Workload to the device: (c, m, R, r_idx, budget) tensors."""
+    to = lambda a: torch.from_numpy(a).to(device)
+    return to(w.c), to(w.m), to(w.R), to(w.r_idx), to(w.budget)

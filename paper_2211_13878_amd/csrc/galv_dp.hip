@@ -1,0 +1,729 @@
+// Batched plan-search dynamic program for gfx950 (MI355X): kernels + C ABI.
+//
+// Paper section 3.3 ("Dynamic Programming Search", Eq. 1): for every layer l,
+// budget column e and strategy s,
+//     C[l][e][s] = c(l,s) + min_{s'} ( C[l-1][e - m(l,s)][s'] + R(s', s) ).
+//
+// How the recurrence is laid out here
+// -----------------------------------
+// The inner minimum does not depend on the memory shift, so each layer is a
+// min-plus product of the (E+1) x S table with the S x S transition matrix:
+//     U_l[e'][s] = c(l,s) + min_{s'} ( C[l-1][e'][s'] + R_l(s', s) )
+//     C[l][e][s] = U_l[e - m(l,s)][s]                (infinity when e < m(l,s))
+// The tables are stored UN-shifted (U_l, and the argmin beside it), strategy
+// major and budget minor, so a wavefront covers 64 consecutive budget columns of
+// one strategy: m(l,s), c(l,s) and R(s',s) are wave-uniform scalars, every
+// global access is a contiguous 512-byte row segment, and the shift is applied
+// when layer l+1 reads column s' at offset -m(l,s').  Each lane keeps the running
+// minima of its budget columns for a whole group of strategies in registers, so
+// the minimum over s' is a serial in-lane loop: no cross-lane reduction, and the
+// lowest-index tie-break falls out of the ascending scan.
+//
+// Two exact arithmetic paths, chosen per instance on the device
+// ------------------------------------------------------------
+//  * fast: cost and argmin are packed into one key, key = cost * 2^k + s'
+//    (k = ceil(log2 S)), carried as a double.  Adding R*2^k + s' to a cost key
+//    and taking the floating minimum is then one v_add_f64 + one v_min_f64 per
+//    candidate and is exact while every key stays below 2^52; +inf is infinity.
+//  * int64: plain 64-bit integer add / compare / select with a separate index,
+//    for instances whose value range does not fit the packed key.
+// A preparation kernel bounds each instance's largest possible plan cost and
+// picks the path; both paths produce bit-identical results.
+//
+// All kernels are plain VALU + global memory; there is no matrix-core work in a
+// min-plus recurrence.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "../../include/galv_dp.h"
+
+namespace {
+
+constexpr int kThreads = 256;          // workgroup = 4 wavefronts of 64
+constexpr int kWave = 64;
+constexpr int kEAlign = 1024;          // budget columns are padded to this
+constexpr int kMaxS = 1024;
+constexpr int64_t kInf = GALV_INF;
+
+thread_local char g_err[512] = "";
+
+galv_status_t fail(galv_status_t code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                  \
+    do {                                                                               \
+        hipError_t e_ = (expr);                                                        \
+        if (e_ != hipSuccess)                                                          \
+            return fail(GALV_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));  \
+    } while (0)
+
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Geometry of one sweep-kernel variant: TS strategies x TE budget columns of
+// running minima per lane, NG strategy groups per workgroup.
+struct Variant {
+    int ts, te, ng;
+};
+
+// Everything the kernels need to find their data.  Passed by value.
+struct Layout {
+    int32_t B, L, S, E_max, nR;
+    int32_t S_pad;        // strategies rounded up to the variant's group size
+    int32_t k_bits;       // index bits in a packed key
+    int32_t tile_e;       // budget columns per workgroup
+    int32_t n_tiles;      // workgroups along the budget axis
+    int64_t lead;         // +inf columns in front of every cost row (fast path)
+    int64_t row;          // elements per cost row: lead + padded columns
+    int64_t e_pad;        // padded budget columns (multiple of kEAlign)
+    double *U[2];         // rolling cost rows   [B][S_pad][row]
+    int32_t *bp;          // argmin, un-shifted  [B][L-1][S][e_pad]
+    double *Rk;           // packed R keys       [B][nR][S][S_pad]
+    double *ck;           // c * 2^k - 2^52      [B][L][S_pad]
+    int32_t *status;      // per instance        [B]
+    int32_t *last;        // best last strategy  [B]
+    const int64_t *c;
+    const int32_t *m;
+    const int64_t *R;
+    const int32_t *r_idx; // may be null
+    const int32_t *budget;
+};
+
+__device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+// ------------------------------------------------------------------ preparation
+//
+// One workgroup per instance.  Checks the value preconditions, bounds the
+// largest cost any plan prefix can reach, picks the arithmetic path and, for the
+// fast path, packs R and c into keys.
+__global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags) {
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int64_t L = a.L, S = a.S, nR = a.nR;
+    const int64_t *c = a.c + (int64_t)b * L * S;
+    const int32_t *m = a.m + (int64_t)b * L * S;
+    const int64_t *R = a.R + (int64_t)b * nR * S * S;
+    const int32_t *ridx = a.r_idx ? a.r_idx + (int64_t)b * L : nullptr;
+
+    __shared__ int bad;
+    __shared__ unsigned long long rmax[64];  // max of each transition matrix (first 64)
+    __shared__ unsigned long long red[kThreads];
+    __shared__ unsigned long long bound_s;
+    if (tid == 0) bad = 0;
+    __syncthreads();
+
+    const int budget = a.budget[b];
+    if (tid == 0 && (budget < 0 || budget > a.E_max)) bad = 1;
+
+    // sum over layers of max_s c(l,s), saturating at 2^62
+    unsigned long long part = 0;
+    for (int64_t l = tid; l < L; l += kThreads) {
+        unsigned long long mx = 0;
+        for (int64_t s = 0; s < S; ++s) {
+            const int64_t v = c[l * S + s];
+            if (v < 0 || v >= kInf) bad = 1;
+            if (m[l * S + s] < 0) bad = 1;
+            if ((unsigned long long)v > mx) mx = (unsigned long long)v;
+        }
+        if (ridx && l >= 1 && (ridx[l] < 0 || ridx[l] >= nR)) bad = 1;
+        part += mx;
+        if (part > (unsigned long long)kInf) part = (unsigned long long)kInf;
+    }
+    red[tid] = part;
+    __syncthreads();
+    for (int w = kThreads / 2; w > 0; w >>= 1) {
+        if (tid < w) {
+            unsigned long long t = red[tid] + red[tid + w];
+            red[tid] = t > (unsigned long long)kInf ? (unsigned long long)kInf : t;
+        }
+        __syncthreads();
+    }
+    if (tid == 0) bound_s = red[0];
+    __syncthreads();
+
+    // plus, for every layer transition, the max of the matrix it uses
+    unsigned long long rsum_all = 0;  // valid in thread 0 only
+    for (int64_t k0 = 0; k0 < nR; k0 += 64) {
+        const int64_t kn = (nR - k0 < 64) ? nR - k0 : 64;
+        for (int64_t k = 0; k < kn; ++k) {
+            unsigned long long mx = 0;
+            const int64_t *Rk = R + (k0 + k) * S * S;
+            for (int64_t i = tid; i < S * S; i += kThreads) {
+                const int64_t v = Rk[i];
+                if (v < 0 || v >= kInf) bad = 1;
+                if ((unsigned long long)v > mx) mx = (unsigned long long)v;
+            }
+            red[tid] = mx;
+            __syncthreads();
+            for (int w = kThreads / 2; w > 0; w >>= 1) {
+                if (tid < w && red[tid + w] > red[tid]) red[tid] = red[tid + w];
+                __syncthreads();
+            }
+            if (tid == 0) rmax[k] = red[0];
+            __syncthreads();
+        }
+        if (tid == 0) {
+            for (int64_t l = 1; l < L; ++l) {
+                const int64_t k = ridx ? ridx[l] : 0;
+                if (k >= k0 && k < k0 + kn) {
+                    rsum_all += rmax[k - k0];
+                    if (rsum_all > (unsigned long long)kInf) rsum_all = (unsigned long long)kInf;
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    __shared__ int status_s;
+    if (tid == 0) {
+        const unsigned long long bound = bound_s + rsum_all;   // each <= 2^62: no wrap
+        int st;
+        if (bad || bound >= (unsigned long long)kInf) {
+            st = GALV_INSTANCE_BAD_VALUE;
+        } else if (!(flags & GALV_DP_FORCE_INT64) &&
+                   bound + 1 <= (1ull << (52 - a.k_bits))) {
+            st = GALV_INSTANCE_OK_FAST;
+        } else {
+            st = GALV_INSTANCE_OK_INT64;
+        }
+        status_s = st;
+        a.status[b] = st;
+    }
+    __syncthreads();
+    if (status_s != GALV_INSTANCE_OK_FAST) return;
+
+    // Packed keys.  R key = R * 2^k + s' (row index); padded columns are +inf so
+    // that they never win and never read past the caller's matrix.
+    const double scale = (double)(1ull << a.k_bits);
+    double *Rk = a.Rk + (int64_t)b * nR * S * a.S_pad;
+    for (int64_t i = tid; i < nR * S * a.S_pad; i += kThreads) {
+        const int64_t s = i % a.S_pad;
+        const int64_t sp = (i / a.S_pad) % S;
+        const int64_t k = i / (a.S_pad * S);
+        Rk[i] = (s < S) ? (double)R[(k * S + sp) * S + s] * scale + (double)sp
+                        : INFINITY;
+    }
+    // c key minus 2^52: added to a key whose exponent was pinned at 2^52.
+    double *ck = a.ck + (int64_t)b * L * a.S_pad;
+    for (int64_t i = tid; i < L * a.S_pad; i += kThreads) {
+        const int64_t s = i % a.S_pad, l = i / a.S_pad;
+        ck[i] = (s < S) ? (double)c[l * S + s] * scale - 0x1p52 : INFINITY;
+    }
+}
+
+// Fill the +inf lead of every cost row once (the lead is never written again).
+__global__ __launch_bounds__(kThreads) void fill_lead_kernel(double *U, int64_t rows, int64_t row,
+                                                             int64_t lead) {
+    const int64_t r = blockIdx.y;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < lead;
+         i += (int64_t)gridDim.x * kThreads)
+        U[r * row + i] = INFINITY;
+    (void)rows;
+}
+
+// Layer 0: U_0[e'][s] = c(0,s) for every e' (the shift by m(0,s) is applied by
+// whoever reads it).  Grid: (e tiles, S, B).
+__global__ __launch_bounds__(kThreads) void init_kernel(Layout a) {
+    const int b = blockIdx.z, s = blockIdx.y;
+    const int st = a.status[b];
+    if (st < 0) return;
+    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e >= a.e_pad) return;
+    double *U = a.U[0] + ((int64_t)b * a.S_pad + s) * a.row + a.lead;
+    if (st == GALV_INSTANCE_OK_FAST) {
+        U[e] = a.ck[((int64_t)b * a.L) * a.S_pad + s] + 0x1p52;
+    } else {
+        reinterpret_cast<int64_t *>(U)[e] = a.c[((int64_t)b * a.L) * a.S + s];
+    }
+}
+
+// ---------------------------------------------------------------- layer sweep
+
+// General 64-bit integer body: one budget column per thread at a time, strategy
+// columns in chunks of CH running (min, argmin) pairs.
+template <int CH>
+__device__ __forceinline__ void sweep_int64(const Layout &a, int l, int b, int budget,
+                                            int64_t tile_start) {
+    const int64_t S = a.S;
+    const int64_t *Uprev = reinterpret_cast<const int64_t *>(a.U[(l - 1) & 1]) +
+                           (int64_t)b * a.S_pad * a.row + a.lead;
+    int64_t *Unew = reinterpret_cast<int64_t *>(a.U[l & 1]) + (int64_t)b * a.S_pad * a.row + a.lead;
+    int32_t *bp = a.bp + ((int64_t)b * (a.L - 1) + (l - 1)) * S * a.e_pad;
+    const int32_t *mprev = a.m + ((int64_t)b * a.L + (l - 1)) * S;
+    const int64_t *cl = a.c + ((int64_t)b * a.L + l) * S;
+    const int r = a.r_idx ? a.r_idx[(int64_t)b * a.L + l] : 0;
+    const int64_t *R = a.R + ((int64_t)b * a.nR + r) * S * S;
+
+    for (int64_t e = tile_start + threadIdx.x; e < tile_start + a.tile_e; e += kThreads) {
+        if (e > budget) continue;
+        for (int64_t s0 = 0; s0 < S; s0 += CH) {
+            int64_t best[CH];
+            int32_t arg[CH];
+#pragma unroll
+            for (int q = 0; q < CH; ++q) {
+                best[q] = kInf;
+                arg[q] = -1;
+            }
+            for (int64_t sp = 0; sp < S; ++sp) {
+                const int64_t shift = mprev[sp];
+                if (shift > budget) continue;             // whole column is infinity
+                const int64_t es = e - shift;
+                const int64_t v = (es >= 0) ? Uprev[sp * a.row + es] : kInf;
+                const int64_t *Rrow = R + sp * S;
+#pragma unroll
+                for (int q = 0; q < CH; ++q) {
+                    const int64_t col = (s0 + q < S) ? s0 + q : S - 1;
+                    const int64_t cand = v + Rrow[col];
+                    if (cand < best[q]) {                 // strict: lowest s' keeps ties
+                        best[q] = cand;
+                        arg[q] = (int32_t)sp;
+                    }
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < CH; ++q) {
+                if (s0 + q < S) {
+                    const bool dead = best[q] >= kInf;
+                    Unew[(s0 + q) * a.row + e] = dead ? kInf : best[q] + cl[s0 + q];
+                    bp[(s0 + q) * a.e_pad + e] = dead ? -1 : arg[q];
+                }
+            }
+        }
+    }
+}
+
+// Fast body: packed keys in doubles.  Lane owns TE budget columns (64 apart) and
+// TS strategy columns; per s' it loads its TE shifted previous-layer values once
+// and reuses them for all TS strategies, with R keys as wave-uniform scalars.
+template <int TS, int TE, int NG>
+__device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int budget,
+                                           int64_t tile_start) {
+    const int wave = uniform(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int g = wave % NG;                       // strategy group of this wave
+    const int esub = wave / NG;                    // budget sub-tile of this wave
+    const int64_t e0 = tile_start + (int64_t)esub * (kWave * TE) + lane;
+    const int64_t s0 = ((int64_t)blockIdx.y * NG + g) * TS;
+    if (s0 >= a.S) return;
+    if (tile_start + (int64_t)esub * (kWave * TE) > budget) return;
+
+    const int64_t S = a.S;
+    const double *Up = a.U[(l - 1) & 1] + (int64_t)b * a.S_pad * a.row + a.lead + e0;
+    double *Un = a.U[l & 1] + ((int64_t)b * a.S_pad + s0) * a.row + a.lead + e0;
+    int32_t *bp = a.bp + (((int64_t)b * (a.L - 1) + (l - 1)) * S + s0) * a.e_pad + e0;
+    const int32_t *mprev = a.m + ((int64_t)b * a.L + (l - 1)) * S;
+    const int r = a.r_idx ? a.r_idx[(int64_t)b * a.L + l] : 0;
+    const double *Rk = a.Rk + ((int64_t)b * a.nR + r) * S * a.S_pad + s0;
+    const double *ck = a.ck + ((int64_t)b * a.L + l) * a.S_pad + s0;
+
+    double acc[TS][TE];
+#pragma unroll
+    for (int s = 0; s < TS; ++s)
+#pragma unroll
+        for (int j = 0; j < TE; ++j) acc[s][j] = INFINITY;
+
+    for (int sp = 0; sp < (int)S; ++sp) {
+        const int shift = mprev[sp];
+        if (shift > budget) continue;                      // whole column is +inf
+        const double *p = Up + (int64_t)sp * a.row - shift;
+        double v[TE];
+#pragma unroll
+        for (int j = 0; j < TE; ++j) v[j] = p[j * kWave];
+        const double *Rrow = Rk + (int64_t)sp * a.S_pad;
+#pragma unroll
+        for (int s = 0; s < TS; ++s) {
+            const double rk = Rrow[s];
+#pragma unroll
+            for (int j = 0; j < TE; ++j) acc[s][j] = fmin(acc[s][j], v[j] + rk);
+        }
+    }
+
+    const uint32_t mask = (1u << a.k_bits) - 1u;
+#pragma unroll
+    for (int s = 0; s < TS; ++s) {
+        if (s0 + s < S) {
+            const double cs = ck[s];
+#pragma unroll
+            for (int j = 0; j < TE; ++j) {
+                const double key = acc[s][j];
+                // Pin the exponent at 2^52: the low mantissa bits are then the
+                // integer key itself, index in the low k bits.
+                const uint64_t bits = (uint64_t)__double_as_longlong(key + 0x1p52);
+                const bool dead = key == INFINITY;
+                const uint64_t cost_bits = bits & ~(uint64_t)mask;
+                Un[(int64_t)s * a.row + j * kWave] = __longlong_as_double((long long)cost_bits) + cs;
+                bp[(int64_t)s * a.e_pad + j * kWave] = dead ? -1 : (int32_t)((uint32_t)bits & mask);
+            }
+        }
+    }
+}
+
+template <int TS, int TE, int NG>
+__global__ __launch_bounds__(kThreads) void sweep_kernel(Layout a, int l) {
+    const int b = blockIdx.z;
+    const int st = a.status[b];
+    if (st < 0) return;
+    const int budget = a.budget[b];
+    const int64_t tile_start = (int64_t)blockIdx.x * a.tile_e;
+    if (tile_start > budget) return;
+    if (st == GALV_INSTANCE_OK_FAST) {
+        sweep_fast<TS, TE, NG>(a, l, b, budget, tile_start);
+    } else {
+        if (blockIdx.y == 0) sweep_int64<8>(a, l, b, budget, tile_start);
+    }
+}
+
+// ------------------------------------------------- final minimum and backtrack
+
+// C[L-1][e][s] from the un-shifted last row, as an integer (GALV_INF if none).
+__device__ __forceinline__ int64_t last_layer_cost(const Layout &a, int b, int st, int64_t e,
+                                                   int64_t s) {
+    const int64_t shift = a.m[((int64_t)b * a.L + (a.L - 1)) * a.S + s];
+    if (shift > e) return kInf;
+    const double *U = a.U[(a.L - 1) & 1] + ((int64_t)b * a.S_pad + s) * a.row + a.lead;
+    if (st == GALV_INSTANCE_OK_FAST) {
+        const double v = U[e - shift];
+        return (v == INFINITY) ? kInf : (int64_t)(v * (1.0 / (double)(1ull << a.k_bits)));
+    }
+    return reinterpret_cast<const int64_t *>(U)[e - shift];
+}
+
+// One workgroup per instance: min over s at e = budget, lowest s first.
+__global__ __launch_bounds__(kThreads) void final_kernel(Layout a, int64_t *best_cost,
+                                                         int32_t *best_last) {
+    const int b = blockIdx.x;
+    const int st = a.status[b];
+    __shared__ int64_t val[kMaxS];
+    if (st >= 0) {
+        const int budget = a.budget[b];
+        for (int s = threadIdx.x; s < a.S; s += kThreads) val[s] = last_layer_cost(a, b, st, budget, s);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int64_t opt = kInf;
+        int32_t last = -1;
+        if (st >= 0)
+            for (int s = 0; s < a.S; ++s)
+                if (val[s] < opt) {
+                    opt = val[s];
+                    last = s;
+                }
+        best_cost[b] = opt;
+        best_last[b] = last;
+        a.last[b] = last;
+    }
+}
+
+// One thread per instance: L dependent loads through the un-shifted argmin table.
+__global__ __launch_bounds__(kWave) void backtrack_kernel(Layout a, int32_t *plan) {
+    const int b = blockIdx.x * kWave + threadIdx.x;
+    if (b >= a.B) return;
+    int32_t *out = plan + (int64_t)b * a.L;
+    int s = a.last[b];
+    if (s < 0) {
+        for (int l = 0; l < a.L; ++l) out[l] = -1;
+        return;
+    }
+    int64_t e = a.budget[b];
+    for (int l = a.L - 1; l >= 1; --l) {
+        out[l] = s;
+        e -= a.m[((int64_t)b * a.L + l) * a.S + s];
+        // A reachable cell always points at a reachable cell; the guard only keeps
+        // the walk inside the table if that invariant were ever broken.
+        if (e < 0 || e > a.E_max) {
+            for (int q = 0; q < a.L; ++q) out[q] = -1;
+            return;
+        }
+        s = a.bp[(((int64_t)b * (a.L - 1) + (l - 1)) * a.S + s) * a.e_pad + e];
+        if (s < 0 || s >= a.S) {
+            for (int q = 0; q < a.L; ++q) out[q] = -1;
+            return;
+        }
+    }
+    out[0] = s;
+}
+
+// Canonical-order tables of one instance.  Grid: (e tiles, L + 1); row L of the
+// grid writes C_last, rows 0..L-1 write the back-pointers of that layer.
+__global__ __launch_bounds__(kThreads) void export_kernel(Layout a, int b, int64_t *C_last,
+                                                          int32_t *bp_out) {
+    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e > a.E_max) return;
+    const int l = blockIdx.y;
+    const int st = a.status[b];
+    const int budget = a.budget[b];
+    const bool live = st >= 0 && e <= budget;
+    if (l == a.L) {
+        for (int s = 0; s < a.S; ++s)
+            C_last[e * a.S + s] = live ? last_layer_cost(a, b, st, e, s) : kInf;
+        return;
+    }
+    if (!bp_out) return;
+    int32_t *dst = bp_out + ((int64_t)l * (a.E_max + 1) + e) * a.S;
+    for (int s = 0; s < a.S; ++s) {
+        int32_t v = -1;
+        if (live && l >= 1) {
+            const int64_t shift = a.m[((int64_t)b * a.L + l) * a.S + s];
+            if (shift <= e)
+                v = a.bp[(((int64_t)b * (a.L - 1) + (l - 1)) * a.S + s) * a.e_pad + (e - shift)];
+        }
+        dst[s] = v;
+    }
+}
+
+// -------------------------------------------------------------------- host side
+
+Variant pick_variant(int S) {
+    if (S <= 8) return {8, 4, 1};
+    if (S <= 16) return {16, 4, 1};
+    if (S <= 22) return {22, 4, 1};
+    if (S <= 32) return {32, 2, 1};
+    if (S <= 44) return {44, 2, 1};
+    if (S <= 64) return {64, 1, 1};
+    return {64, 1, 2};
+}
+
+using SweepFn = void (*)(Layout, int);
+SweepFn sweep_for(const Variant &v) {
+    if (v.ts == 8) return sweep_kernel<8, 4, 1>;
+    if (v.ts == 16) return sweep_kernel<16, 4, 1>;
+    if (v.ts == 22) return sweep_kernel<22, 4, 1>;
+    if (v.ts == 32) return sweep_kernel<32, 2, 1>;
+    if (v.ts == 44) return sweep_kernel<44, 2, 1>;
+    if (v.ng == 1) return sweep_kernel<64, 1, 1>;
+    return sweep_kernel<64, 1, 2>;
+}
+
+}  // namespace
+
+struct galv_dp {
+    galv_dp_desc_t desc;
+    Variant var;
+    Layout lay;        // workspace pointers filled, input pointers set per solve
+    size_t ws_bytes;
+    int device;
+    int groups_y;      // grid.y of the sweep
+    bool solved;
+};
+
+namespace {
+
+struct Plan {
+    Variant var;
+    Layout lay;
+    size_t off_U[2], off_bp, off_Rk, off_ck, off_status, off_last, total;
+    int groups_y;
+};
+
+galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
+    if (!d) return fail(GALV_ERR_INVALID_ARG, "desc is NULL");
+    if (d->n_instances < 1 || d->n_layers < 1 || d->n_strategies < 1 || d->max_budget < 0 ||
+        d->n_transition < 1)
+        return fail(GALV_ERR_INVALID_ARG,
+                    "desc: need n_instances>=1, n_layers>=1, n_strategies>=1, max_budget>=0, "
+                    "n_transition>=1 (got %d %d %d %d %d)",
+                    d->n_instances, d->n_layers, d->n_strategies, d->max_budget, d->n_transition);
+    if (d->n_strategies > kMaxS)
+        return fail(GALV_ERR_INVALID_ARG, "n_strategies %d exceeds the limit %d", d->n_strategies,
+                    kMaxS);
+    if (d->flags & ~GALV_DP_FORCE_INT64) return fail(GALV_ERR_INVALID_ARG, "unknown flag bits");
+    if (d->n_instances > 65535)
+        return fail(GALV_ERR_RANGE, "n_instances %d exceeds the grid limit 65535", d->n_instances);
+    if (d->max_budget > (1 << 30))
+        return fail(GALV_ERR_RANGE, "max_budget %d exceeds 2^30", d->max_budget);
+
+    memset(p, 0, sizeof *p);
+    Variant v = pick_variant(d->n_strategies);
+    Layout &a = p->lay;
+    a.B = d->n_instances;
+    a.L = d->n_layers;
+    a.S = d->n_strategies;
+    a.E_max = d->max_budget;
+    a.nR = d->n_transition;
+    const int group = v.ts * v.ng;
+    p->groups_y = (a.S + group - 1) / group;
+    a.S_pad = p->groups_y * group;
+    int k = 0;
+    while ((1 << k) < a.S) ++k;
+    a.k_bits = k;
+    a.tile_e = kWave * v.te * (4 / v.ng);
+    a.e_pad = (int64_t)round_up((size_t)a.E_max + 1, kEAlign);
+    a.n_tiles = (int32_t)((a.E_max + a.tile_e) / a.tile_e);   // ceil((E_max+1)/tile_e)
+    a.lead = (int64_t)round_up((size_t)a.E_max + 1, 64);
+    a.row = a.lead + a.e_pad;
+    p->var = v;
+
+    // Sizes in long double first, to reject anything that would overflow size_t math.
+    const long double approx = (long double)a.B * a.S_pad * a.row * 16 +
+                               (long double)a.B * (a.L - 1) * a.S * a.e_pad * 4 +
+                               (long double)a.B * a.nR * a.S * a.S_pad * 8;
+    if (approx > 1e15L) return fail(GALV_ERR_RANGE, "tables of %.3Lg bytes cannot be indexed", approx);
+
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = off;
+        off = round_up(off + bytes, 256);
+        return at;
+    };
+    const size_t u_bytes = (size_t)a.B * a.S_pad * a.row * sizeof(double);
+    p->off_U[0] = take(u_bytes);
+    p->off_U[1] = take(u_bytes);
+    p->off_bp = take((size_t)a.B * (a.L - 1) * a.S * a.e_pad * sizeof(int32_t));
+    p->off_Rk = take((size_t)a.B * a.nR * a.S * a.S_pad * sizeof(double));
+    p->off_ck = take((size_t)a.B * a.L * a.S_pad * sizeof(double));
+    p->off_status = take((size_t)a.B * sizeof(int32_t));
+    p->off_last = take((size_t)a.B * sizeof(int32_t));
+    p->total = off;
+    return GALV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+galv_status_t galv_dp_workspace_bytes(const galv_dp_desc_t *desc, size_t *bytes) {
+    if (!bytes) return fail(GALV_ERR_INVALID_ARG, "bytes is NULL");
+    Plan p;
+    galv_status_t st = make_plan(desc, &p);
+    if (st != GALV_OK) return st;
+    *bytes = p.total;
+    return GALV_OK;
+}
+
+galv_status_t galv_dp_create(const galv_dp_desc_t *desc, void *workspace_dev,
+                             size_t workspace_bytes, galv_dp_t **out) {
+    if (!out) return fail(GALV_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    Plan p;
+    galv_status_t st = make_plan(desc, &p);
+    if (st != GALV_OK) return st;
+    if (!workspace_dev) return fail(GALV_ERR_WORKSPACE, "workspace is NULL");
+    if (reinterpret_cast<uintptr_t>(workspace_dev) % 256 != 0)
+        return fail(GALV_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    if (workspace_bytes < p.total)
+        return fail(GALV_ERR_WORKSPACE, "workspace of %zu bytes is smaller than the %zu needed",
+                    workspace_bytes, p.total);
+
+    galv_dp *h = new (std::nothrow) galv_dp;
+    if (!h) return fail(GALV_ERR_INVALID_ARG, "out of host memory");
+    h->desc = *desc;
+    h->var = p.var;
+    h->lay = p.lay;
+    h->ws_bytes = p.total;
+    h->groups_y = p.groups_y;
+    h->solved = false;
+    char *ws = static_cast<char *>(workspace_dev);
+    Layout &a = h->lay;
+    a.U[0] = reinterpret_cast<double *>(ws + p.off_U[0]);
+    a.U[1] = reinterpret_cast<double *>(ws + p.off_U[1]);
+    a.bp = reinterpret_cast<int32_t *>(ws + p.off_bp);
+    a.Rk = reinterpret_cast<double *>(ws + p.off_Rk);
+    a.ck = reinterpret_cast<double *>(ws + p.off_ck);
+    a.status = reinterpret_cast<int32_t *>(ws + p.off_status);
+    a.last = reinterpret_cast<int32_t *>(ws + p.off_last);
+
+    hipError_t e = hipGetDevice(&h->device);
+    if (e == hipSuccess) {
+        const int64_t rows = (int64_t)a.B * a.S_pad;
+        // grid.y is limited to 65535 rows per launch
+        for (int64_t r0 = 0; r0 < rows && e == hipSuccess; r0 += 65535) {
+            const int64_t n = rows - r0 < 65535 ? rows - r0 : 65535;
+            const int gx = (int)((a.lead + kThreads - 1) / kThreads < 64
+                                     ? (a.lead + kThreads - 1) / kThreads
+                                     : 64);
+            for (int u = 0; u < 2; ++u)
+                fill_lead_kernel<<<dim3(gx, (unsigned)n), kThreads, 0, nullptr>>>(
+                    a.U[u] + r0 * a.row, n, a.row, a.lead);
+            e = hipGetLastError();
+        }
+        if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+    }
+    if (e != hipSuccess) {
+        delete h;
+        return fail(GALV_ERR_HIP, "workspace initialisation failed: %s", hipGetErrorString(e));
+    }
+    *out = h;
+    return GALV_OK;
+}
+
+galv_status_t galv_dp_solve_batched(galv_dp_t *h, const int64_t *c_dev, const int32_t *m_dev,
+                                    const int64_t *R_dev, const int32_t *r_idx_dev,
+                                    const int32_t *budget_dev, int64_t *best_cost_dev,
+                                    int32_t *best_last_dev, void *stream) {
+    if (!h) return fail(GALV_ERR_INVALID_ARG, "handle is NULL");
+    if (!c_dev || !m_dev || !R_dev || !budget_dev || !best_cost_dev || !best_last_dev)
+        return fail(GALV_ERR_INVALID_ARG, "a required device pointer is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Layout &a = h->lay;
+    a.c = c_dev;
+    a.m = m_dev;
+    a.R = R_dev;
+    a.r_idx = r_idx_dev;
+    a.budget = budget_dev;
+    h->solved = false;
+
+    prep_kernel<<<a.B, kThreads, 0, st>>>(a, h->desc.flags);
+    init_kernel<<<dim3((unsigned)(a.e_pad / kThreads), a.S, a.B), kThreads, 0, st>>>(a);
+    SweepFn sweep = sweep_for(h->var);
+    const dim3 grid(a.n_tiles, h->groups_y, a.B);
+    for (int l = 1; l < a.L; ++l) sweep<<<grid, kThreads, 0, st>>>(a, l);
+    final_kernel<<<a.B, kThreads, 0, st>>>(a, best_cost_dev, best_last_dev);
+    HIP_TRY(hipGetLastError());
+    h->solved = true;
+    return GALV_OK;
+}
+
+galv_status_t galv_dp_backtrack(galv_dp_t *h, int32_t *plan_dev, void *stream) {
+    if (!h) return fail(GALV_ERR_INVALID_ARG, "handle is NULL");
+    if (!plan_dev) return fail(GALV_ERR_INVALID_ARG, "plan_dev is NULL");
+    if (!h->solved) return fail(GALV_ERR_STATE, "backtrack before a successful solve");
+    const Layout &a = h->lay;
+    backtrack_kernel<<<(a.B + kWave - 1) / kWave, kWave, 0, static_cast<hipStream_t>(stream)>>>(
+        a, plan_dev);
+    HIP_TRY(hipGetLastError());
+    return GALV_OK;
+}
+
+galv_status_t galv_dp_export_tables(galv_dp_t *h, int32_t instance, int64_t *C_last_dev,
+                                    int32_t *bp_dev, void *stream) {
+    if (!h) return fail(GALV_ERR_INVALID_ARG, "handle is NULL");
+    if (!C_last_dev) return fail(GALV_ERR_INVALID_ARG, "C_last_dev is NULL");
+    if (!h->solved) return fail(GALV_ERR_STATE, "export before a successful solve");
+    const Layout &a = h->lay;
+    if (instance < 0 || instance >= a.B)
+        return fail(GALV_ERR_INVALID_ARG, "instance %d out of range [0, %d)", instance, a.B);
+    if (a.L + 1 > 65535) return fail(GALV_ERR_RANGE, "too many layers to export");
+    const dim3 grid((unsigned)((a.E_max + kThreads) / kThreads), a.L + 1);
+    export_kernel<<<grid, kThreads, 0, static_cast<hipStream_t>(stream)>>>(a, instance, C_last_dev,
+                                                                          bp_dev);
+    HIP_TRY(hipGetLastError());
+    return GALV_OK;
+}
+
+galv_status_t galv_dp_get_status(galv_dp_t *h, int32_t *status_dev, void *stream) {
+    if (!h) return fail(GALV_ERR_INVALID_ARG, "handle is NULL");
+    if (!status_dev) return fail(GALV_ERR_INVALID_ARG, "status_dev is NULL");
+    if (!h->solved) return fail(GALV_ERR_STATE, "status before a successful solve");
+    HIP_TRY(hipMemcpyAsync(status_dev, h->lay.status, (size_t)h->lay.B * sizeof(int32_t),
+                           hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)));
+    return GALV_OK;
+}
+
+galv_status_t galv_dp_destroy(galv_dp_t *h) {
+    delete h;
+    return GALV_OK;
+}
+
+const char *galv_dp_last_error(void) { return g_err; }
+
+}  // extern "C"
