@@ -63,6 +63,9 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload index 0..4 (default 3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--force-int64", action="store_true", help="time the general integer kernels")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known traffic: 1 GiB read, "
+                         "1 GiB written) so that rocprofv3 FETCH_SIZE / WRITE_SIZE readings can be scaled")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; instances are independent, so more GPUs "
@@ -87,6 +90,13 @@ def main():
         sol.solve(*dev)
         sol.backtrack()
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -15,7 +15,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libgalvdp.so")
+# GALV_DP_LIB lets a developer point at another build of the same library.
+LIB_PATH = os.environ.get("GALV_DP_LIB") or os.path.join(_HERE, "libgalvdp.so")
 
 GALV_INF = 1 << 62
 GALV_OK = 0

@@ -332,13 +332,12 @@ __device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int bu
 #pragma unroll
         for (int j = 0; j < TE; ++j) acc[s][j] = INFINITY;
 
-    for (int sp = 0; sp < (int)S; ++sp) {
-        const int shift = mprev[sp];
-        if (shift > budget) continue;                      // whole column is +inf
-        const double *p = Up + (int64_t)sp * a.row - shift;
-        double v[TE];
-#pragma unroll
-        for (int j = 0; j < TE; ++j) v[j] = p[j * kWave];
+    // Former-layer strategies in blocks of 64: one coalesced load brings the 64
+    // shifts m(l-1, s'), a ballot keeps the usable ones (a shift beyond the
+    // budget makes the whole column +inf), and the loop walks the set bits in
+    // ascending order.  The values of the next usable s' are requested before the
+    // arithmetic of the current one, so their latency hides behind it.
+    auto accumulate = [&](int sp, const double (&v)[TE]) {
         const double *Rrow = Rk + (int64_t)sp * a.S_pad;
 #pragma unroll
         for (int s = 0; s < TS; ++s) {
@@ -346,6 +345,31 @@ __device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int bu
 #pragma unroll
             for (int j = 0; j < TE; ++j) acc[s][j] = fmin(acc[s][j], v[j] + rk);
         }
+    };
+    for (int blk = 0; blk < (int)S; blk += kWave) {
+        const int shv = (blk + lane < (int)S) ? mprev[blk + lane] : 0x7fffffff;
+        unsigned long long todo = __ballot(shv <= budget);
+        if (todo == 0) continue;
+        int j = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        double cur[TE], nxt[TE];
+        {
+            const double *p = Up + (int64_t)(blk + j) * a.row - __builtin_amdgcn_readlane(shv, j);
+#pragma unroll
+            for (int q = 0; q < TE; ++q) cur[q] = p[q * kWave];
+        }
+        while (todo != 0) {
+            const int jn = __builtin_ctzll(todo);
+            todo &= todo - 1;
+            const double *p = Up + (int64_t)(blk + jn) * a.row - __builtin_amdgcn_readlane(shv, jn);
+#pragma unroll
+            for (int q = 0; q < TE; ++q) nxt[q] = p[q * kWave];
+            accumulate(blk + j, cur);
+#pragma unroll
+            for (int q = 0; q < TE; ++q) cur[q] = nxt[q];
+            j = jn;
+        }
+        accumulate(blk + j, cur);
     }
 
     const uint32_t mask = (1u << a.k_bits) - 1u;
@@ -483,25 +507,40 @@ __global__ __launch_bounds__(kThreads) void export_kernel(Layout a, int b, int64
 
 // -------------------------------------------------------------------- host side
 
-Variant pick_variant(int S) {
-    if (S <= 8) return {8, 4, 1};
-    if (S <= 16) return {16, 4, 1};
-    if (S <= 22) return {22, 4, 1};
-    if (S <= 32) return {32, 2, 1};
-    if (S <= 44) return {44, 2, 1};
-    if (S <= 64) return {64, 1, 1};
-    return {64, 1, 2};
-}
+// Sweep variants, in ascending order of the strategies one workgroup covers
+// (TS * NG).  The first one that covers S is used; larger S use the last one with
+// several strategy groups along grid.y.  <TS, TE, NG>: TS * TE running minima per
+// lane bound the VGPR count (2 registers each) and with it the waves per SIMD.
+#ifndef GALV_V0
+#define GALV_V0 8, 4, 1
+#define GALV_V1 16, 4, 1
+#define GALV_V2 22, 4, 1
+#define GALV_V3 32, 2, 1
+#define GALV_V4 44, 2, 1
+#define GALV_V5 64, 1, 1
+#define GALV_V6 64, 1, 2
+#endif
 
 using SweepFn = void (*)(Layout, int);
-SweepFn sweep_for(const Variant &v) {
-    if (v.ts == 8) return sweep_kernel<8, 4, 1>;
-    if (v.ts == 16) return sweep_kernel<16, 4, 1>;
-    if (v.ts == 22) return sweep_kernel<22, 4, 1>;
-    if (v.ts == 32) return sweep_kernel<32, 2, 1>;
-    if (v.ts == 44) return sweep_kernel<44, 2, 1>;
-    if (v.ng == 1) return sweep_kernel<64, 1, 1>;
-    return sweep_kernel<64, 1, 2>;
+struct VariantEntry {
+    Variant v;
+    SweepFn fn;
+};
+template <int TS, int TE, int NG>
+VariantEntry variant_entry() {
+    static_assert(NG == 1 || NG == 2 || NG == 4, "strategy groups per workgroup");
+    return {{TS, TE, NG}, sweep_kernel<TS, TE, NG>};
+}
+
+const VariantEntry &pick_variant(int S) {
+    static const VariantEntry table[] = {
+        variant_entry<GALV_V0>(), variant_entry<GALV_V1>(), variant_entry<GALV_V2>(),
+        variant_entry<GALV_V3>(), variant_entry<GALV_V4>(), variant_entry<GALV_V5>(),
+        variant_entry<GALV_V6>()};
+    constexpr int n = sizeof table / sizeof table[0];
+    for (int i = 0; i < n; ++i)
+        if (S <= table[i].v.ts * table[i].v.ng) return table[i];
+    return table[n - 1];
 }
 
 }  // namespace
@@ -509,6 +548,7 @@ SweepFn sweep_for(const Variant &v) {
 struct galv_dp {
     galv_dp_desc_t desc;
     Variant var;
+    SweepFn sweep;
     Layout lay;        // workspace pointers filled, input pointers set per solve
     size_t ws_bytes;
     int device;
@@ -520,6 +560,7 @@ namespace {
 
 struct Plan {
     Variant var;
+    SweepFn sweep;
     Layout lay;
     size_t off_U[2], off_bp, off_Rk, off_ck, off_status, off_last, total;
     int groups_y;
@@ -543,7 +584,9 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
         return fail(GALV_ERR_RANGE, "max_budget %d exceeds 2^30", d->max_budget);
 
     memset(p, 0, sizeof *p);
-    Variant v = pick_variant(d->n_strategies);
+    const VariantEntry &ve = pick_variant(d->n_strategies);
+    const Variant v = ve.v;
+    p->sweep = ve.fn;
     Layout &a = p->lay;
     a.B = d->n_instances;
     a.L = d->n_layers;
@@ -618,6 +661,7 @@ galv_status_t galv_dp_create(const galv_dp_desc_t *desc, void *workspace_dev,
     if (!h) return fail(GALV_ERR_INVALID_ARG, "out of host memory");
     h->desc = *desc;
     h->var = p.var;
+    h->sweep = p.sweep;
     h->lay = p.lay;
     h->ws_bytes = p.total;
     h->groups_y = p.groups_y;
@@ -674,7 +718,7 @@ galv_status_t galv_dp_solve_batched(galv_dp_t *h, const int64_t *c_dev, const in
 
     prep_kernel<<<a.B, kThreads, 0, st>>>(a, h->desc.flags);
     init_kernel<<<dim3((unsigned)(a.e_pad / kThreads), a.S, a.B), kThreads, 0, st>>>(a);
-    SweepFn sweep = sweep_for(h->var);
+    SweepFn sweep = h->sweep;
     const dim3 grid(a.n_tiles, h->groups_y, a.B);
     for (int l = 1; l < a.L; ++l) sweep<<<grid, kThreads, 0, st>>>(a, l);
     final_kernel<<<a.B, kThreads, 0, st>>>(a, best_cost_dev, best_last_dev);
