@@ -25,8 +25,7 @@
  *    inputs alive and unchanged until the stream has passed the calls that read
  *    them (m_dev and budget_dev until the last backtrack / export of that solve).
  *  - solve / backtrack / export only enqueue work on `stream`; they never
- *    synchronise and never allocate.  galv_dp_create enqueues a one-time
- *    workspace initialisation on the default stream and waits for it.
+ *    synchronise and never allocate.  galv_dp_create touches no device memory.
  *  - Errors in host-visible arguments are returned as codes (never exceptions,
  *    never abort); galv_dp_last_error() gives a thread-local message.
  *  - Input VALUES live on the device and cannot be checked synchronously: a
@@ -74,9 +73,12 @@ typedef struct {
                                   an instance's values would allow the faster exact path */
 
 /* Per-instance status codes written by solve (see galv_dp_get_status). */
-#define GALV_INSTANCE_OK_FAST 0   /* solved by the exact floating-key kernels          */
-#define GALV_INSTANCE_OK_INT64 1  /* solved by the general 64-bit integer kernels      */
-#define GALV_INSTANCE_BAD_VALUE (-1) /* a value violates the preconditions above       */
+#define GALV_INSTANCE_OK_FAST 0      /* packed-key kernels, costs stored in 32 bits (all plan
+                                        costs plus the largest R stay below 2^31)          */
+#define GALV_INSTANCE_OK_INT64 1     /* general 64-bit integer kernels                      */
+#define GALV_INSTANCE_OK_FAST_WIDE 2 /* packed-key kernels, costs stored in 64 bits (cost
+                                        times the next power of two >= S stays below 2^52)  */
+#define GALV_INSTANCE_BAD_VALUE (-1) /* a value violates the preconditions above            */
 
 /*
  * Bytes of device workspace a handle for `desc` needs (rolling cost rows,

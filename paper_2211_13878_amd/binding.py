@@ -22,7 +22,8 @@ GALV_INF = 1 << 62
 GALV_OK = 0
 GALV_ERR_INVALID_ARG, GALV_ERR_WORKSPACE, GALV_ERR_RANGE, GALV_ERR_HIP, GALV_ERR_STATE = 1, 2, 3, 4, 5
 GALV_DP_FORCE_INT64 = 1
-GALV_INSTANCE_OK_FAST, GALV_INSTANCE_OK_INT64, GALV_INSTANCE_BAD_VALUE = 0, 1, -1
+GALV_INSTANCE_OK_FAST, GALV_INSTANCE_OK_INT64, GALV_INSTANCE_OK_FAST_WIDE = 0, 1, 2
+GALV_INSTANCE_BAD_VALUE = -1
 
 EXPORTS = ("galv_dp_workspace_bytes", "galv_dp_create", "galv_dp_solve_batched",
            "galv_dp_backtrack", "galv_dp_export_tables", "galv_dp_get_status",

@@ -13,22 +13,27 @@
 // The tables are stored UN-shifted (U_l, and the argmin beside it), strategy
 // major and budget minor, so a wavefront covers 64 consecutive budget columns of
 // one strategy: m(l,s), c(l,s) and R(s',s) are wave-uniform scalars, every
-// global access is a contiguous 512-byte row segment, and the shift is applied
-// when layer l+1 reads column s' at offset -m(l,s').  Each lane keeps the running
-// minima of its budget columns for a whole group of strategies in registers, so
-// the minimum over s' is a serial in-lane loop: no cross-lane reduction, and the
-// lowest-index tie-break falls out of the ascending scan.
+// global access is a contiguous row segment, and the shift is applied when layer
+// l+1 reads column s' at offset -m(l,s').  Each lane keeps the running minima of
+// its budget columns for a group of strategies in registers, so the minimum over
+// s' is a serial in-lane loop: no cross-lane reduction, and the lowest-index
+// tie-break falls out of the key order.
 //
-// Two exact arithmetic paths, chosen per instance on the device
-// ------------------------------------------------------------
-//  * fast: cost and argmin are packed into one key, key = cost * 2^k + s'
-//    (k = ceil(log2 S)), carried as a double.  Adding R*2^k + s' to a cost key
-//    and taking the floating minimum is then one v_add_f64 + one v_min_f64 per
-//    candidate and is exact while every key stays below 2^52; +inf is infinity.
+// Exact arithmetic paths, chosen per instance on the device
+// ---------------------------------------------------------
+//  * fast: cost and argmin are packed into one integer key = cost * 2^k + s'
+//    (k = ceil(log2 S)) that lives in the mantissa of a double whose exponent is
+//    pinned: K = 2^52 + key.  Adding the plain double R * 2^k + s' to a cost key
+//    and taking the floating minimum is one v_add_f64 + one v_min_f64 per
+//    candidate, exact while K stays below 2^53, and the minimum of keys is the
+//    minimum cost with the lowest s' among equals.  Two storage widths:
+//      - narrow: costs below 2^31 are stored as uint32 (infinity = 2^31), 4 bytes
+//        per table cell;
+//      - wide: the cost key itself is stored as a double (infinity = +inf).
 //  * int64: plain 64-bit integer add / compare / select with a separate index,
-//    for instances whose value range does not fit the packed key.
+//    for instances whose value range does not fit a 52-bit key.
 // A preparation kernel bounds each instance's largest possible plan cost and
-// picks the path; both paths produce bit-identical results.
+// picks the path; all paths produce bit-identical results.
 //
 // All kernels are plain VALU + global memory; there is no matrix-core work in a
 // min-plus recurrence.
@@ -49,7 +54,13 @@ constexpr int kThreads = 256;          // workgroup = 4 wavefronts of 64
 constexpr int kWave = 64;
 constexpr int kEAlign = 1024;          // budget columns are padded to this
 constexpr int kMaxS = 1024;
+#ifndef GALV_DEPTH
+#define GALV_DEPTH 4
+#endif
+constexpr int kDepth = GALV_DEPTH;      // previous-layer loads kept in flight per wave
 constexpr int64_t kInf = GALV_INF;
+constexpr uint32_t kInf32 = 0x80000000u;             // infinity of the narrow storage
+constexpr uint64_t kBias = 0x4330000000000000ull;    // bit pattern of 2^52
 
 thread_local char g_err[512] = "";
 
@@ -83,13 +94,15 @@ struct Layout {
     int32_t k_bits;       // index bits in a packed key
     int32_t tile_e;       // budget columns per workgroup
     int32_t n_tiles;      // workgroups along the budget axis
-    int64_t lead;         // +inf columns in front of every cost row (fast path)
-    int64_t row;          // elements per cost row: lead + padded columns
+    int64_t lead;         // infinity columns in front of every cost row (fast paths)
+    int64_t row;          // cells per cost row: lead + padded columns (8 bytes reserved each)
     int64_t e_pad;        // padded budget columns (multiple of kEAlign)
-    double *U[2];         // rolling cost rows   [B][S_pad][row]
+    char *U[2];           // rolling cost rows   [B][S_pad][row] of 8-byte slots
     int32_t *bp;          // argmin, un-shifted  [B][L-1][S][e_pad]
-    double *Rk;           // packed R keys       [B][nR][S][S_pad]
-    double *ck;           // c * 2^k - 2^52      [B][L][S_pad]
+    double *Rk;           // R * 2^k + s'        [B][nR][S][S_pad] (+inf in padded columns)
+    uint64_t *ck;         // per-mode c(l,s)     [B][L][S_pad]
+    uint64_t *vlist;      // usable strategies of each layer, ascending: shift << 32 | s'  [B][L][S]
+    int32_t *nvalid;      // how many of them    [B][L]
     int32_t *status;      // per instance        [B]
     int32_t *last;        // best last strategy  [B]
     const int64_t *c;
@@ -101,11 +114,73 @@ struct Layout {
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// Read-only view through the constant address space: data that no thread writes
+// while the kernel runs (inputs, tables packed by the preparation kernel).  With a
+// wave-uniform address such loads go through the scalar cache into SGPRs.
+template <class T>
+using ConstPtr = const T __attribute__((address_space(4))) *;
+template <class T>
+__device__ __forceinline__ ConstPtr<T> as_const(const T *p) {
+    return (ConstPtr<T>)(uintptr_t)p;
+}
+
+// ------------------------------------------------------------- storage policies
+//
+// How a cost is kept in the rolling rows, and how it becomes the biased key
+// K = 2^52 + cost * 2^k that the arithmetic works on (and back).
+struct Narrow {
+    using Cell = uint32_t;
+    static __device__ __forceinline__ double dead_key(int k) {
+        return __longlong_as_double((long long)(kBias | ((uint64_t)kInf32 << k)));
+    }
+    static __device__ __forceinline__ double to_key(Cell x, int k) {
+        return __longlong_as_double((long long)(kBias | ((uint64_t)x << k)));
+    }
+    // From the reduced key: new cell = cost + c(l,s), argmin index (-1 if unreachable).
+    static __device__ __forceinline__ void finish(double key, uint64_t cs, int k, uint32_t mask,
+                                                  Cell &cell, int32_t &arg) {
+        const uint64_t bits = (uint64_t)__double_as_longlong(key);
+        const uint32_t cost = (uint32_t)(bits >> k);          // >= 2^31 exactly when unreachable
+        const uint32_t sum = cost + (uint32_t)cs;             // < 2^32 by the range check
+        cell = sum < kInf32 ? sum : kInf32;
+        arg = (int32_t)((uint32_t)bits & mask) | ((int32_t)cost >> 31);
+    }
+    static __device__ __forceinline__ Cell first_layer(uint64_t cs) { return (Cell)cs; }
+    static __device__ __forceinline__ Cell infinity() { return kInf32; }
+    static __device__ __forceinline__ int64_t to_int64(Cell x, int) {
+        return x >= kInf32 ? kInf : (int64_t)x;
+    }
+};
+
+struct Wide {
+    using Cell = double;
+    static __device__ __forceinline__ double dead_key(int) { return INFINITY; }
+    static __device__ __forceinline__ double to_key(Cell x, int) { return x; }
+    static __device__ __forceinline__ void finish(double key, uint64_t cs, int, uint32_t mask,
+                                                  Cell &cell, int32_t &arg) {
+        const uint64_t bits = (uint64_t)__double_as_longlong(key);
+        const uint32_t hi = (uint32_t)(bits >> 32);
+        // strip the index, add c * 2^k (an unbiased double): the sum keeps the bias
+        cell = __longlong_as_double((long long)(bits & ~(uint64_t)mask)) +
+               __longlong_as_double((long long)cs);
+        // bit 29 of the high word is set for +inf (0x7ff..) and clear for 2^52 <= K < 2^53
+        arg = (int32_t)((uint32_t)bits & mask) | ((int32_t)(hi << 2) >> 31);
+    }
+    static __device__ __forceinline__ Cell first_layer(uint64_t cs) {
+        return __longlong_as_double((long long)cs) + 0x1p52;
+    }
+    static __device__ __forceinline__ Cell infinity() { return INFINITY; }
+    static __device__ __forceinline__ int64_t to_int64(Cell x, int k) {
+        if (x == INFINITY) return kInf;
+        return (int64_t)((((uint64_t)__double_as_longlong(x)) & 0x000fffffffffffffull) >> k);
+    }
+};
+
 // ------------------------------------------------------------------ preparation
 //
 // One workgroup per instance.  Checks the value preconditions, bounds the
 // largest cost any plan prefix can reach, picks the arithmetic path and, for the
-// fast path, packs R and c into keys.
+// fast paths, packs R and c and lists the usable strategies of every layer.
 __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags) {
     const int b = blockIdx.x;
     const int tid = threadIdx.x;
@@ -114,9 +189,10 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
     const int32_t *m = a.m + (int64_t)b * L * S;
     const int64_t *R = a.R + (int64_t)b * nR * S * S;
     const int32_t *ridx = a.r_idx ? a.r_idx + (int64_t)b * L : nullptr;
+    const unsigned long long cap = (unsigned long long)kInf;
 
     __shared__ int bad;
-    __shared__ unsigned long long rmax[64];  // max of each transition matrix (first 64)
+    __shared__ unsigned long long rmax[64];  // max of each transition matrix (64 at a time)
     __shared__ unsigned long long red[kThreads];
     __shared__ unsigned long long bound_s;
     if (tid == 0) bad = 0;
@@ -137,14 +213,14 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
         }
         if (ridx && l >= 1 && (ridx[l] < 0 || ridx[l] >= nR)) bad = 1;
         part += mx;
-        if (part > (unsigned long long)kInf) part = (unsigned long long)kInf;
+        if (part > cap) part = cap;
     }
     red[tid] = part;
     __syncthreads();
     for (int w = kThreads / 2; w > 0; w >>= 1) {
         if (tid < w) {
-            unsigned long long t = red[tid] + red[tid + w];
-            red[tid] = t > (unsigned long long)kInf ? (unsigned long long)kInf : t;
+            const unsigned long long t = red[tid] + red[tid + w];
+            red[tid] = t > cap ? cap : t;
         }
         __syncthreads();
     }
@@ -152,14 +228,14 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
     __syncthreads();
 
     // plus, for every layer transition, the max of the matrix it uses
-    unsigned long long rsum_all = 0;  // valid in thread 0 only
+    unsigned long long rsum = 0, rmax_all = 0;  // valid in thread 0 only
     for (int64_t k0 = 0; k0 < nR; k0 += 64) {
         const int64_t kn = (nR - k0 < 64) ? nR - k0 : 64;
         for (int64_t k = 0; k < kn; ++k) {
             unsigned long long mx = 0;
-            const int64_t *Rk = R + (k0 + k) * S * S;
+            const int64_t *Rm = R + (k0 + k) * S * S;
             for (int64_t i = tid; i < S * S; i += kThreads) {
-                const int64_t v = Rk[i];
+                const int64_t v = Rm[i];
                 if (v < 0 || v >= kInf) bad = 1;
                 if ((unsigned long long)v > mx) mx = (unsigned long long)v;
             }
@@ -169,15 +245,18 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
                 if (tid < w && red[tid + w] > red[tid]) red[tid] = red[tid + w];
                 __syncthreads();
             }
-            if (tid == 0) rmax[k] = red[0];
+            if (tid == 0) {
+                rmax[k] = red[0];
+                if (red[0] > rmax_all) rmax_all = red[0];
+            }
             __syncthreads();
         }
         if (tid == 0) {
             for (int64_t l = 1; l < L; ++l) {
                 const int64_t k = ridx ? ridx[l] : 0;
                 if (k >= k0 && k < k0 + kn) {
-                    rsum_all += rmax[k - k0];
-                    if (rsum_all > (unsigned long long)kInf) rsum_all = (unsigned long long)kInf;
+                    rsum += rmax[k - k0];
+                    if (rsum > cap) rsum = cap;
                 }
             }
         }
@@ -186,13 +265,16 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
 
     __shared__ int status_s;
     if (tid == 0) {
-        const unsigned long long bound = bound_s + rsum_all;   // each <= 2^62: no wrap
+        const unsigned long long bound = bound_s + rsum;   // each <= 2^62: no wrap
         int st;
-        if (bad || bound >= (unsigned long long)kInf) {
+        if (bad || bound >= cap) {
             st = GALV_INSTANCE_BAD_VALUE;
-        } else if (!(flags & GALV_DP_FORCE_INT64) &&
-                   bound + 1 <= (1ull << (52 - a.k_bits))) {
-            st = GALV_INSTANCE_OK_FAST;
+        } else if (flags & GALV_DP_FORCE_INT64) {
+            st = GALV_INSTANCE_OK_INT64;
+        } else if (bound + rmax_all < kInf32) {
+            st = GALV_INSTANCE_OK_FAST;         // costs, and infinity + R, fit 32 bits
+        } else if (bound + 1 <= (1ull << (52 - a.k_bits))) {
+            st = GALV_INSTANCE_OK_FAST_WIDE;    // keys fit the 52-bit mantissa
         } else {
             st = GALV_INSTANCE_OK_INT64;
         }
@@ -200,9 +282,10 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
         a.status[b] = st;
     }
     __syncthreads();
-    if (status_s != GALV_INSTANCE_OK_FAST) return;
+    const int st = status_s;
+    if (st != GALV_INSTANCE_OK_FAST && st != GALV_INSTANCE_OK_FAST_WIDE) return;
 
-    // Packed keys.  R key = R * 2^k + s' (row index); padded columns are +inf so
+    // R key = R * 2^k + s' (s' = row = former strategy); padded columns are +inf so
     // that they never win and never read past the caller's matrix.
     const double scale = (double)(1ull << a.k_bits);
     double *Rk = a.Rk + (int64_t)b * nR * S * a.S_pad;
@@ -210,40 +293,66 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
         const int64_t s = i % a.S_pad;
         const int64_t sp = (i / a.S_pad) % S;
         const int64_t k = i / (a.S_pad * S);
-        Rk[i] = (s < S) ? (double)R[(k * S + sp) * S + s] * scale + (double)sp
-                        : INFINITY;
+        Rk[i] = (s < S) ? (double)R[(k * S + sp) * S + s] * scale + (double)sp : INFINITY;
     }
-    // c key minus 2^52: added to a key whose exponent was pinned at 2^52.
-    double *ck = a.ck + (int64_t)b * L * a.S_pad;
+    // c(l,s) in the form the epilogue adds: the integer itself (narrow) or the
+    // double c * 2^k (wide).
+    uint64_t *ck = a.ck + (int64_t)b * L * a.S_pad;
     for (int64_t i = tid; i < L * a.S_pad; i += kThreads) {
         const int64_t s = i % a.S_pad, l = i / a.S_pad;
-        ck[i] = (s < S) ? (double)c[l * S + s] * scale - 0x1p52 : INFINITY;
+        const int64_t v = (s < S) ? c[l * S + s] : 0;
+        ck[i] = (st == GALV_INSTANCE_OK_FAST)
+                    ? (uint64_t)v
+                    : (uint64_t)__double_as_longlong((double)v * scale);
     }
-}
-
-// Fill the +inf lead of every cost row once (the lead is never written again).
-__global__ __launch_bounds__(kThreads) void fill_lead_kernel(double *U, int64_t rows, int64_t row,
-                                                             int64_t lead) {
-    const int64_t r = blockIdx.y;
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < lead;
-         i += (int64_t)gridDim.x * kThreads)
-        U[r * row + i] = INFINITY;
-    (void)rows;
+    // Per layer, the strategies whose memory fits the budget at all, in ascending
+    // order, with their shift: the sweep of the next layer walks this list instead
+    // of all S columns (a column that never fits is infinity everywhere).
+    for (int64_t l = tid; l < L; l += kThreads) {
+        uint64_t *lst = a.vlist + ((int64_t)b * L + l) * S;
+        int n = 0;
+        for (int s = 0; s < (int)S; ++s) {
+            const int sh = m[l * S + s];
+            if (sh <= budget) lst[n++] = ((uint64_t)(uint32_t)sh << 32) | (uint32_t)s;
+        }
+        a.nvalid[(int64_t)b * L + l] = n;
+    }
 }
 
 // Layer 0: U_0[e'][s] = c(0,s) for every e' (the shift by m(0,s) is applied by
-// whoever reads it).  Grid: (e tiles, S, B).
+// whoever reads it), and the infinity lead in front of both rolling rows of the
+// strategy.  Grid: (row cells / 256, S, B).
 __global__ __launch_bounds__(kThreads) void init_kernel(Layout a) {
     const int b = blockIdx.z, s = blockIdx.y;
     const int st = a.status[b];
     if (st < 0) return;
-    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (e >= a.e_pad) return;
-    double *U = a.U[0] + ((int64_t)b * a.S_pad + s) * a.row + a.lead;
+    const int64_t x = (int64_t)blockIdx.x * kThreads + threadIdx.x;   // cell within the row
+    if (x >= a.row) return;
+    const int64_t base = ((int64_t)b * a.S_pad + s) * a.row * 8;
+    if (st == GALV_INSTANCE_OK_INT64) {
+        if (x >= a.lead)
+            reinterpret_cast<int64_t *>(a.U[0] + base)[x] = a.c[((int64_t)b * a.L) * a.S + s];
+        return;
+    }
+    const uint64_t cs = a.ck[((int64_t)b * a.L) * a.S_pad + s];
     if (st == GALV_INSTANCE_OK_FAST) {
-        U[e] = a.ck[((int64_t)b * a.L) * a.S_pad + s] + 0x1p52;
+        uint32_t *u0 = reinterpret_cast<uint32_t *>(a.U[0] + base);
+        uint32_t *u1 = reinterpret_cast<uint32_t *>(a.U[1] + base);
+        if (x < a.lead) {
+            u0[x] = Narrow::infinity();
+            u1[x] = Narrow::infinity();
+        } else {
+            u0[x] = Narrow::first_layer(cs);
+        }
     } else {
-        reinterpret_cast<int64_t *>(U)[e] = a.c[((int64_t)b * a.L) * a.S + s];
+        double *u0 = reinterpret_cast<double *>(a.U[0] + base);
+        double *u1 = reinterpret_cast<double *>(a.U[1] + base);
+        if (x < a.lead) {
+            u0[x] = Wide::infinity();
+            u1[x] = Wide::infinity();
+        } else {
+            u0[x] = Wide::first_layer(cs);
+        }
     }
 }
 
@@ -302,12 +411,68 @@ __device__ __forceinline__ void sweep_int64(const Layout &a, int l, int b, int b
     }
 }
 
-// Fast body: packed keys in doubles.  Lane owns TE budget columns (64 apart) and
-// TS strategy columns; per s' it loads its TE shifted previous-layer values once
-// and reuses them for all TS strategies, with R keys as wave-uniform scalars.
-template <int TS, int TE, int NG>
+// acc[j] = min(acc[j], v[j] + rk) on packed keys: one v_add_f64 and one v_min_f64
+// per candidate, rk a wave-uniform SGPR pair.  Written as one asm block per
+// strategy so that each needs only TE temporaries (left to itself the scheduler
+// hoists every add of a row above the minima and spills), with the adds ahead of
+// the minima so that no instruction waits on the one just issued.
+template <int TE>
+__device__ __forceinline__ void minplus(double (&acc)[TE], const double (&v)[TE], double rk) {
+    static_assert(TE == 1 || TE == 2 || TE == 4, "budget columns per lane");
+    if constexpr (TE == 1) {
+        double t0;
+        asm("v_add_f64 %1, %2, %3\n\tv_min_f64 %0, %0, %1"
+            : "+v"(acc[0]), "=&v"(t0)
+            : "v"(v[0]), "s"(rk));
+    } else if constexpr (TE == 2) {
+        double t0, t1;
+        asm("v_add_f64 %2, %4, %6\n\tv_add_f64 %3, %5, %6\n\t"
+            "v_min_f64 %0, %0, %2\n\tv_min_f64 %1, %1, %3"
+            : "+v"(acc[0]), "+v"(acc[1]), "=&v"(t0), "=&v"(t1)
+            : "v"(v[0]), "v"(v[1]), "s"(rk));
+    } else {
+        double t0, t1, t2, t3;
+        asm("v_add_f64 %4, %8, %12\n\tv_add_f64 %5, %9, %12\n\t"
+            "v_add_f64 %6, %10, %12\n\tv_add_f64 %7, %11, %12\n\t"
+            "v_min_f64 %0, %0, %4\n\tv_min_f64 %1, %1, %5\n\t"
+            "v_min_f64 %2, %2, %6\n\tv_min_f64 %3, %3, %7"
+            : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "=&v"(t0), "=&v"(t1),
+              "=&v"(t2), "=&v"(t3)
+            : "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "s"(rk));
+    }
+}
+
+// A group of R keys in SGPRs: 8 * NCH doubles fetched by NCH scalar loads of 16
+// dwords.  The loads are issued by hand (the compiler would wait for each right
+// where it issues it); rgroup_await makes every later use depend on the wait.
+typedef double double8 __attribute__((ext_vector_type(8)));
+template <int NCH>
+struct RGroup {
+    double8 c[NCH];
+};
+__device__ __forceinline__ void rgroup_request(RGroup<1> &g, ConstPtr<double> p) {
+    asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=&s"(g.c[0]) : "s"(p));
+}
+__device__ __forceinline__ void rgroup_request(RGroup<2> &g, ConstPtr<double> p) {
+    asm volatile("s_load_dwordx16 %0, %2, 0x0\n\ts_load_dwordx16 %1, %2, 0x40"
+                 : "=&s"(g.c[0]), "=&s"(g.c[1])
+                 : "s"(p));
+}
+__device__ __forceinline__ void rgroup_await(RGroup<1> &g) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(g.c[0]));
+}
+__device__ __forceinline__ void rgroup_await(RGroup<2> &g) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(g.c[0]), "+s"(g.c[1]));
+}
+
+// Fast body.  Lane owns TE budget columns (64 apart) and TS strategy columns; per
+// usable s' it loads its TE shifted previous-layer cells once and reuses them for
+// all TS strategies, with the R keys as wave-uniform scalars.
+template <int TS, int TE, int NG, class Store>
 __device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int budget,
                                            int64_t tile_start) {
+    using Cell = typename Store::Cell;
+    constexpr int64_t kPerSlot = 8 / sizeof(Cell);     // cells per reserved 8-byte slot
     const int wave = uniform(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int g = wave % NG;                       // strategy group of this wave
@@ -318,82 +483,106 @@ __device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int bu
     if (tile_start + (int64_t)esub * (kWave * TE) > budget) return;
 
     const int64_t S = a.S;
-    const double *Up = a.U[(l - 1) & 1] + (int64_t)b * a.S_pad * a.row + a.lead + e0;
-    double *Un = a.U[l & 1] + ((int64_t)b * a.S_pad + s0) * a.row + a.lead + e0;
+    const int k = a.k_bits;
+    const int64_t pitch = a.row * kPerSlot;        // cells between rows of two strategies
+    const Cell *Up = reinterpret_cast<const Cell *>(a.U[(l - 1) & 1]) +
+                     (int64_t)b * a.S_pad * pitch + a.lead + e0;
+    Cell *Un = reinterpret_cast<Cell *>(a.U[l & 1]) + ((int64_t)b * a.S_pad + s0) * pitch +
+               a.lead + e0;
     int32_t *bp = a.bp + (((int64_t)b * (a.L - 1) + (l - 1)) * S + s0) * a.e_pad + e0;
-    const int32_t *mprev = a.m + ((int64_t)b * a.L + (l - 1)) * S;
     const int r = a.r_idx ? a.r_idx[(int64_t)b * a.L + l] : 0;
-    const double *Rk = a.Rk + ((int64_t)b * a.nR + r) * S * a.S_pad + s0;
-    const double *ck = a.ck + ((int64_t)b * a.L + l) * a.S_pad + s0;
+    const ConstPtr<double> Rk = as_const(a.Rk + ((int64_t)b * a.nR + r) * S * a.S_pad + s0);
+    const ConstPtr<uint64_t> ck = as_const(a.ck + ((int64_t)b * a.L + l) * a.S_pad + s0);
 
     double acc[TS][TE];
+    const double dead = Store::dead_key(k);
 #pragma unroll
     for (int s = 0; s < TS; ++s)
 #pragma unroll
-        for (int j = 0; j < TE; ++j) acc[s][j] = INFINITY;
+        for (int j = 0; j < TE; ++j) acc[s][j] = dead;
 
-    // Former-layer strategies in blocks of 64: one coalesced load brings the 64
-    // shifts m(l-1, s'), a ballot keeps the usable ones (a shift beyond the
-    // budget makes the whole column +inf), and the loop walks the set bits in
-    // ascending order.  The values of the next usable s' are requested before the
-    // arithmetic of the current one, so their latency hides behind it.
-    auto accumulate = [&](int sp, const double (&v)[TE]) {
-        const double *Rrow = Rk + (int64_t)sp * a.S_pad;
+    // Walk the usable former-layer strategies (list built by the preparation
+    // kernel; entries are wave-uniform scalars).  Two software pipelines run
+    // under the arithmetic:
+    //  * the shifted previous-layer cells of entry i + kDepth are requested
+    //    while entry i is reduced (vector loads, kDepth - 1 entries of cover);
+    //  * the R keys of a row arrive in groups of up to 16 doubles through explicit
+    //    scalar loads into one of two SGPR buffers: the next group is requested
+    //    before the current one is consumed and awaited after it.
+    const ConstPtr<uint64_t> vl = as_const(a.vlist + ((int64_t)b * a.L + (l - 1)) * S);
+    const int n = as_const(a.nvalid)[(int64_t)b * a.L + (l - 1)];
+    if (n > 0) {
+        constexpr int kChunks = TS > 8 ? 2 : 1;            // scalar loads per group
+        constexpr int kGroup = 8 * kChunks;                // doubles per group
+        constexpr int kGroups = (TS + kGroup - 1) / kGroup;
+        static_assert((kDepth * kGroups) % 2 == 0, "buffer roles must repeat every loop trip");
+        Cell v[kDepth][TE];
+        int sps[kDepth];
+        RGroup<kChunks> buf[2];
+        // Requests are never conditional (past the end they repeat the last entry,
+        // which is cached) so that no wait is needed where control flow joins.
+        auto request = [&](int q, int i) {
+            const uint64_t ent = vl[i < n ? i : n - 1];
+            sps[q] = (int)(uint32_t)ent;
+            const Cell *p = Up + (int64_t)(uint32_t)ent * pitch - (int64_t)(ent >> 32);
 #pragma unroll
-        for (int s = 0; s < TS; ++s) {
-            const double rk = Rrow[s];
+            for (int j = 0; j < TE; ++j) v[q][j] = p[j * kWave];
+        };
+        // One entry: for each group, request the following group (of this entry or
+        // of the next entry's row), reduce the current one, then await the request.
+        auto reduce_entry = [&](int q) {
+            double key[TE];
 #pragma unroll
-            for (int j = 0; j < TE; ++j) acc[s][j] = fmin(acc[s][j], v[j] + rk);
+            for (int j = 0; j < TE; ++j) key[j] = Store::to_key(v[q][j], k);
+#pragma unroll
+            for (int gr = 0; gr < kGroups; ++gr) {
+                const int t = q * kGroups + gr;
+                const int qn = (gr + 1 < kGroups) ? q : (q + 1) % kDepth;
+                const int gn = (gr + 1 < kGroups) ? gr + 1 : 0;
+                rgroup_request(buf[(t + 1) & 1], Rk + (int64_t)sps[qn] * a.S_pad + gn * kGroup);
+#pragma unroll
+                for (int x = 0; x < kGroup; ++x)
+                    if (gr * kGroup + x < TS)
+                        minplus<TE>(acc[gr * kGroup + x], key, buf[t & 1].c[x / 8][x % 8]);
+                rgroup_await(buf[(t + 1) & 1]);
+            }
+        };
+#pragma unroll
+        for (int q = 0; q < kDepth; ++q) request(q, q);
+        rgroup_request(buf[0], Rk + (int64_t)sps[0] * a.S_pad);
+        rgroup_await(buf[0]);
+        int i = 0;
+        for (; i + kDepth <= n; i += kDepth) {
+#pragma unroll
+            for (int q = 0; q < kDepth; ++q) {
+                reduce_entry(q);
+                request(q, i + q + kDepth);
+            }
         }
-    };
-    for (int blk = 0; blk < (int)S; blk += kWave) {
-        const int shv = (blk + lane < (int)S) ? mprev[blk + lane] : 0x7fffffff;
-        unsigned long long todo = __ballot(shv <= budget);
-        if (todo == 0) continue;
-        int j = __builtin_ctzll(todo);
-        todo &= todo - 1;
-        double cur[TE], nxt[TE];
-        {
-            const double *p = Up + (int64_t)(blk + j) * a.row - __builtin_amdgcn_readlane(shv, j);
 #pragma unroll
-            for (int q = 0; q < TE; ++q) cur[q] = p[q * kWave];
-        }
-        while (todo != 0) {
-            const int jn = __builtin_ctzll(todo);
-            todo &= todo - 1;
-            const double *p = Up + (int64_t)(blk + jn) * a.row - __builtin_amdgcn_readlane(shv, jn);
-#pragma unroll
-            for (int q = 0; q < TE; ++q) nxt[q] = p[q * kWave];
-            accumulate(blk + j, cur);
-#pragma unroll
-            for (int q = 0; q < TE; ++q) cur[q] = nxt[q];
-            j = jn;
-        }
-        accumulate(blk + j, cur);
+        for (int q = 0; q < kDepth - 1; ++q)
+            if (i + q < n) reduce_entry(q);
     }
 
-    const uint32_t mask = (1u << a.k_bits) - 1u;
+    const uint32_t mask = (1u << k) - 1u;
 #pragma unroll
     for (int s = 0; s < TS; ++s) {
         if (s0 + s < S) {
-            const double cs = ck[s];
+            const uint64_t cs = ck[s];
 #pragma unroll
             for (int j = 0; j < TE; ++j) {
-                const double key = acc[s][j];
-                // Pin the exponent at 2^52: the low mantissa bits are then the
-                // integer key itself, index in the low k bits.
-                const uint64_t bits = (uint64_t)__double_as_longlong(key + 0x1p52);
-                const bool dead = key == INFINITY;
-                const uint64_t cost_bits = bits & ~(uint64_t)mask;
-                Un[(int64_t)s * a.row + j * kWave] = __longlong_as_double((long long)cost_bits) + cs;
-                bp[(int64_t)s * a.e_pad + j * kWave] = dead ? -1 : (int32_t)((uint32_t)bits & mask);
+                Cell cell;
+                int32_t arg;
+                Store::finish(acc[s][j], cs, k, mask, cell, arg);
+                Un[(int64_t)s * pitch + j * kWave] = cell;
+                bp[(int64_t)s * a.e_pad + j * kWave] = arg;
             }
         }
     }
 }
 
-template <int TS, int TE, int NG>
-__global__ __launch_bounds__(kThreads) void sweep_kernel(Layout a, int l) {
+template <int TS, int TE, int NG, int WPE>
+__global__ __launch_bounds__(kThreads, WPE) void sweep_kernel(Layout a, int l) {
     const int b = blockIdx.z;
     const int st = a.status[b];
     if (st < 0) return;
@@ -401,7 +590,9 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(Layout a, int l) {
     const int64_t tile_start = (int64_t)blockIdx.x * a.tile_e;
     if (tile_start > budget) return;
     if (st == GALV_INSTANCE_OK_FAST) {
-        sweep_fast<TS, TE, NG>(a, l, b, budget, tile_start);
+        sweep_fast<TS, TE, NG, Narrow>(a, l, b, budget, tile_start);
+    } else if (st == GALV_INSTANCE_OK_FAST_WIDE) {
+        sweep_fast<TS, TE, NG, Wide>(a, l, b, budget, tile_start);
     } else {
         if (blockIdx.y == 0) sweep_int64<8>(a, l, b, budget, tile_start);
     }
@@ -414,12 +605,13 @@ __device__ __forceinline__ int64_t last_layer_cost(const Layout &a, int b, int s
                                                    int64_t s) {
     const int64_t shift = a.m[((int64_t)b * a.L + (a.L - 1)) * a.S + s];
     if (shift > e) return kInf;
-    const double *U = a.U[(a.L - 1) & 1] + ((int64_t)b * a.S_pad + s) * a.row + a.lead;
-    if (st == GALV_INSTANCE_OK_FAST) {
-        const double v = U[e - shift];
-        return (v == INFINITY) ? kInf : (int64_t)(v * (1.0 / (double)(1ull << a.k_bits)));
-    }
-    return reinterpret_cast<const int64_t *>(U)[e - shift];
+    const char *U = a.U[(a.L - 1) & 1] + ((int64_t)b * a.S_pad + s) * a.row * 8;
+    const int64_t x = a.lead + e - shift;
+    if (st == GALV_INSTANCE_OK_FAST)
+        return Narrow::to_int64(reinterpret_cast<const uint32_t *>(U)[x], a.k_bits);
+    if (st == GALV_INSTANCE_OK_FAST_WIDE)
+        return Wide::to_int64(reinterpret_cast<const double *>(U)[x], a.k_bits);
+    return reinterpret_cast<const int64_t *>(U)[x];
 }
 
 // One workgroup per instance: min over s at e = budget, lowest s first.
@@ -509,16 +701,17 @@ __global__ __launch_bounds__(kThreads) void export_kernel(Layout a, int b, int64
 
 // Sweep variants, in ascending order of the strategies one workgroup covers
 // (TS * NG).  The first one that covers S is used; larger S use the last one with
-// several strategy groups along grid.y.  <TS, TE, NG>: TS * TE running minima per
-// lane bound the VGPR count (2 registers each) and with it the waves per SIMD.
+// several strategy groups along grid.y.  <TS, TE, NG, WPE>: TS * TE running minima
+// per lane (2 VGPRs each) for WPE resident waves per SIMD (512 VGPRs / WPE each).
+// Measured on MI355X: small register tiles at 3-5 waves per SIMD beat large tiles
+// at 2 (the scalar R loads and the table loads are hidden by occupancy).
 #ifndef GALV_V0
-#define GALV_V0 8, 4, 1
-#define GALV_V1 16, 4, 1
-#define GALV_V2 22, 4, 1
-#define GALV_V3 32, 2, 1
-#define GALV_V4 44, 2, 1
-#define GALV_V5 64, 1, 1
-#define GALV_V6 64, 1, 2
+#define GALV_V0 8, 4, 1, 4
+#define GALV_V1 16, 2, 1, 5
+#define GALV_V2 22, 2, 1, 3
+#define GALV_V3 16, 2, 2, 5
+#define GALV_V4 22, 2, 2, 4
+#define GALV_V5 16, 2, 2, 5
 #endif
 
 using SweepFn = void (*)(Layout, int);
@@ -526,17 +719,16 @@ struct VariantEntry {
     Variant v;
     SweepFn fn;
 };
-template <int TS, int TE, int NG>
+template <int TS, int TE, int NG, int WPE>
 VariantEntry variant_entry() {
     static_assert(NG == 1 || NG == 2 || NG == 4, "strategy groups per workgroup");
-    return {{TS, TE, NG}, sweep_kernel<TS, TE, NG>};
+    return {{TS, TE, NG}, sweep_kernel<TS, TE, NG, WPE>};
 }
 
 const VariantEntry &pick_variant(int S) {
     static const VariantEntry table[] = {
         variant_entry<GALV_V0>(), variant_entry<GALV_V1>(), variant_entry<GALV_V2>(),
-        variant_entry<GALV_V3>(), variant_entry<GALV_V4>(), variant_entry<GALV_V5>(),
-        variant_entry<GALV_V6>()};
+        variant_entry<GALV_V3>(), variant_entry<GALV_V4>(), variant_entry<GALV_V5>()};
     constexpr int n = sizeof table / sizeof table[0];
     for (int i = 0; i < n; ++i)
         if (S <= table[i].v.ts * table[i].v.ng) return table[i];
@@ -551,7 +743,6 @@ struct galv_dp {
     SweepFn sweep;
     Layout lay;        // workspace pointers filled, input pointers set per solve
     size_t ws_bytes;
-    int device;
     int groups_y;      // grid.y of the sweep
     bool solved;
 };
@@ -562,7 +753,7 @@ struct Plan {
     Variant var;
     SweepFn sweep;
     Layout lay;
-    size_t off_U[2], off_bp, off_Rk, off_ck, off_status, off_last, total;
+    size_t off_U[2], off_bp, off_Rk, off_ck, off_vlist, off_nvalid, off_status, off_last, total;
     int groups_y;
 };
 
@@ -618,12 +809,15 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
         off = round_up(off + bytes, 256);
         return at;
     };
-    const size_t u_bytes = (size_t)a.B * a.S_pad * a.row * sizeof(double);
+    const size_t u_bytes = (size_t)a.B * a.S_pad * a.row * 8;
     p->off_U[0] = take(u_bytes);
     p->off_U[1] = take(u_bytes);
     p->off_bp = take((size_t)a.B * (a.L - 1) * a.S * a.e_pad * sizeof(int32_t));
-    p->off_Rk = take((size_t)a.B * a.nR * a.S * a.S_pad * sizeof(double));
-    p->off_ck = take((size_t)a.B * a.L * a.S_pad * sizeof(double));
+    // + slack: a group of R keys is fetched whole even when it straddles the row end
+    p->off_Rk = take((size_t)a.B * a.nR * a.S * a.S_pad * sizeof(double) + 1024);
+    p->off_ck = take((size_t)a.B * a.L * a.S_pad * sizeof(uint64_t));
+    p->off_vlist = take((size_t)a.B * a.L * a.S * sizeof(uint64_t));
+    p->off_nvalid = take((size_t)a.B * a.L * sizeof(int32_t));
     p->off_status = take((size_t)a.B * sizeof(int32_t));
     p->off_last = take((size_t)a.B * sizeof(int32_t));
     p->total = off;
@@ -668,34 +862,15 @@ galv_status_t galv_dp_create(const galv_dp_desc_t *desc, void *workspace_dev,
     h->solved = false;
     char *ws = static_cast<char *>(workspace_dev);
     Layout &a = h->lay;
-    a.U[0] = reinterpret_cast<double *>(ws + p.off_U[0]);
-    a.U[1] = reinterpret_cast<double *>(ws + p.off_U[1]);
+    a.U[0] = ws + p.off_U[0];
+    a.U[1] = ws + p.off_U[1];
     a.bp = reinterpret_cast<int32_t *>(ws + p.off_bp);
     a.Rk = reinterpret_cast<double *>(ws + p.off_Rk);
-    a.ck = reinterpret_cast<double *>(ws + p.off_ck);
+    a.ck = reinterpret_cast<uint64_t *>(ws + p.off_ck);
+    a.vlist = reinterpret_cast<uint64_t *>(ws + p.off_vlist);
+    a.nvalid = reinterpret_cast<int32_t *>(ws + p.off_nvalid);
     a.status = reinterpret_cast<int32_t *>(ws + p.off_status);
     a.last = reinterpret_cast<int32_t *>(ws + p.off_last);
-
-    hipError_t e = hipGetDevice(&h->device);
-    if (e == hipSuccess) {
-        const int64_t rows = (int64_t)a.B * a.S_pad;
-        // grid.y is limited to 65535 rows per launch
-        for (int64_t r0 = 0; r0 < rows && e == hipSuccess; r0 += 65535) {
-            const int64_t n = rows - r0 < 65535 ? rows - r0 : 65535;
-            const int gx = (int)((a.lead + kThreads - 1) / kThreads < 64
-                                     ? (a.lead + kThreads - 1) / kThreads
-                                     : 64);
-            for (int u = 0; u < 2; ++u)
-                fill_lead_kernel<<<dim3(gx, (unsigned)n), kThreads, 0, nullptr>>>(
-                    a.U[u] + r0 * a.row, n, a.row, a.lead);
-            e = hipGetLastError();
-        }
-        if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
-    }
-    if (e != hipSuccess) {
-        delete h;
-        return fail(GALV_ERR_HIP, "workspace initialisation failed: %s", hipGetErrorString(e));
-    }
     *out = h;
     return GALV_OK;
 }
@@ -717,10 +892,9 @@ galv_status_t galv_dp_solve_batched(galv_dp_t *h, const int64_t *c_dev, const in
     h->solved = false;
 
     prep_kernel<<<a.B, kThreads, 0, st>>>(a, h->desc.flags);
-    init_kernel<<<dim3((unsigned)(a.e_pad / kThreads), a.S, a.B), kThreads, 0, st>>>(a);
-    SweepFn sweep = h->sweep;
+    init_kernel<<<dim3((unsigned)((a.row + kThreads - 1) / kThreads), a.S, a.B), kThreads, 0, st>>>(a);
     const dim3 grid(a.n_tiles, h->groups_y, a.B);
-    for (int l = 1; l < a.L; ++l) sweep<<<grid, kThreads, 0, st>>>(a, l);
+    for (int l = 1; l < a.L; ++l) h->sweep<<<grid, kThreads, 0, st>>>(a, l);
     final_kernel<<<a.B, kThreads, 0, st>>>(a, best_cost_dev, best_last_dev);
     HIP_TRY(hipGetLastError());
     h->solved = true;

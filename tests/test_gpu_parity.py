@@ -201,6 +201,19 @@ def test_large_values_take_int64_path_and_agree():
     assert list(status) == [binding.GALV_INSTANCE_OK_INT64] * 3 + [binding.GALV_INSTANCE_OK_FAST]
 
 
+def test_mid_range_values_take_wide_storage():
+    """Costs around 2^35 do not fit the 32-bit table cells but do fit a 52-bit key:
+    the library keeps the packed-key kernels with 64-bit cells.  The last instance
+    sits just below the narrow limit (sum of maxima + largest R < 2^31)."""
+    w = workloads.random_workload(23, 4, 7, 12, 900, nR=2, m_range=(0, 150),
+                                  c_range=(0, 1 << 35), r_range=(0, 1 << 33), infeasible=0.1)
+    w.c[3] = w.c[3] % ((1 << 31) // 7 - (1 << 26))
+    w.R[3] = w.R[3] % ((1 << 26) // 7)
+    cost, last, plan, status = check_against_oracle(w, table_instances=[0, 1, 3])
+    assert list(status) == [binding.GALV_INSTANCE_OK_FAST_WIDE] * 3 + [binding.GALV_INSTANCE_OK_FAST]
+    assert (cost[cost < INF] > (1 << 31)).any()
+
+
 def test_bad_values_are_reported_not_solved():
     w = workloads.random_workload(3, 5, 4, 5, 50, m_range=(0, 9), c_range=(0, 9), r_range=(0, 9))
     w.c[0, 1, 2] = -1
