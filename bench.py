@@ -31,7 +31,13 @@ sys.path.insert(0, ROOT)
 VALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12      # 39.3
 HBM_PEAK_GBS = 8000.0
 OPS_PER_CANDIDATE = 2                              # v_add_f64 + v_min_f64
-BYTES_PER_STATE = 20                               # 8 B read + 8 B write of the cost row, 4 B back-pointer
+# table bytes per state: cost cell read + cost cell written + int32 back-pointer written
+BYTES_PER_STATE = {0: 4 + 4 + 4, 2: 8 + 8 + 4, 1: 8 + 8 + 4}   # by per-instance status code
+
+
+# HBM bytes per sweep launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by the
+# same counter's reading for a 1 GiB copy (profiles/sweep_kernel_config<N>.md); None where not measured.
+MEASURED_TRAFFIC_BYTES = {3: 727198395, 4: 3506273195}
 
 
 def cpu_baseline(w, seconds_hint=20.0):
@@ -125,7 +131,9 @@ def main():
     #                                                           includes prep/init/final, < 1 %)
     ops = OPS_PER_CANDIDATE if not args.force_int64 else 6
     achieved = exact / n_launch * ops / (sweep_ms * 1e-3) / 1e12
-    hbm_gbs = states / w.L * BYTES_PER_STATE / (sweep_ms * 1e-3) / 1e9
+    per_state = [BYTES_PER_STATE.get(int(st), 0) for st in status]
+    hbm_bytes = sum(p * (int(e) + 1) * w.S for p, e in zip(per_state, w.budget))   # per layer
+    hbm_gbs = hbm_bytes / (sweep_ms * 1e-3) / 1e9
 
     out = {
         "metric": "dp_cell_updates_per_sec",
@@ -147,10 +155,12 @@ def main():
         "instances_feasible": int((cost < binding.GALV_INF).sum()),
         "roofline": {"bound": "alu", "kernel": "sweep_kernel", "achieved": achieved,
                      "peak": VALU_PEAK_TLANEOPS, "unit": "Tlane-op/s",
-                     "frac": achieved / VALU_PEAK_TLANEOPS, "traffic": None,
+                     "frac": achieved / VALU_PEAK_TLANEOPS,
+                     "traffic": None if args.force_int64 else MEASURED_TRAFFIC_BYTES.get(args.config),
                      "launch_ms": sweep_ms, "lane_ops_per_candidate": ops,
                      "hbm": {"achieved": hbm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                             "frac": hbm_gbs / HBM_PEAK_GBS, "bytes_per_state": BYTES_PER_STATE}},
+                             "frac": hbm_gbs / HBM_PEAK_GBS, "bytes_per_launch": hbm_bytes,
+                             "bytes_per_state": max(per_state)}},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
