@@ -55,7 +55,7 @@ constexpr int kWave = 64;
 constexpr int kEAlign = 1024;          // budget columns are padded to this
 constexpr int kMaxS = 1024;
 #ifndef GALV_DEPTH
-#define GALV_DEPTH 4
+#define GALV_DEPTH 2
 #endif
 constexpr int kDepth = GALV_DEPTH;      // previous-layer loads kept in flight per wave
 constexpr int64_t kInf = GALV_INF;
@@ -703,15 +703,16 @@ __global__ __launch_bounds__(kThreads) void export_kernel(Layout a, int b, int64
 // (TS * NG).  The first one that covers S is used; larger S use the last one with
 // several strategy groups along grid.y.  <TS, TE, NG, WPE>: TS * TE running minima
 // per lane (2 VGPRs each) for WPE resident waves per SIMD (512 VGPRs / WPE each).
-// Measured on MI355X: small register tiles at 3-5 waves per SIMD beat large tiles
-// at 2 (the scalar R loads and the table loads are hidden by occupancy).
+// Measured on MI355X: small register tiles at 6-8 waves per SIMD with a shallow
+// prefetch beat large tiles at 2-4 waves with a deep one (the scalar R loads and
+// the table loads are hidden by occupancy).
 #ifndef GALV_V0
-#define GALV_V0 8, 4, 1, 4
-#define GALV_V1 16, 2, 1, 5
-#define GALV_V2 22, 2, 1, 3
-#define GALV_V3 16, 2, 2, 5
-#define GALV_V4 22, 2, 2, 4
-#define GALV_V5 16, 2, 2, 5
+#define GALV_V0 8, 2, 1, 8
+#define GALV_V1 16, 2, 1, 6
+#define GALV_V2 11, 2, 2, 8
+#define GALV_V3 16, 2, 2, 6
+#define GALV_V4 11, 2, 4, 8
+#define GALV_V5 16, 2, 2, 6
 #endif
 
 using SweepFn = void (*)(Layout, int);
