@@ -123,6 +123,28 @@ galv_status_t galv_dp_solve_batched(galv_dp_t *h, const int64_t *c_dev, const in
 galv_status_t galv_dp_backtrack(galv_dp_t *h, int32_t *plan_dev, void *stream);
 
 /*
+ * All budgets at once.  The table has "at most e" semantics (the optimal-substructure
+ * argument of section 3.3: the optimum of a smaller budget E' <= E is a sub-problem
+ * of the same table), so one solve at budget[b] answers every smaller budget, as
+ * when one model is planned for several memory limits (Table 1's 8/12/16/20 GB columns).
+ *   best_cost_dev [B][E_max+1] out int64  min_s C[L-1][e][s]; GALV_INF if none or e > budget[b]
+ *   best_last_dev [B][E_max+1] out int32  lowest minimising s, -1 if none.  May be NULL.
+ */
+galv_status_t galv_dp_best_per_budget(galv_dp_t *h, int64_t *best_cost_dev, int32_t *best_last_dev,
+                                      void *stream);
+
+/*
+ * Optimal plans for n_queries (instance, budget) pairs of the last solve, each as
+ * if that instance had been solved with that budget (0 <= budget <= budget[b]).
+ *   instance_dev [Q] int32, budget_dev [Q] int32
+ *   cost_dev     [Q]    out int64  optimum or GALV_INF.  May be NULL.
+ *   plan_dev     [Q][L] out int32  all -1 when no plan fits or the query is out of range.
+ */
+galv_status_t galv_dp_backtrack_queries(galv_dp_t *h, int32_t n_queries, const int32_t *instance_dev,
+                                        const int32_t *budget_dev, int64_t *cost_dev,
+                                        int32_t *plan_dev, void *stream);
+
+/*
  * Test / debug: write one instance's tables of the last solve in canonical
  * order, as the recurrence defines them.
  *   C_last_dev [E_max+1][S]      int64  C[L-1][e][s]; GALV_INF when unreachable or e > budget

@@ -26,7 +26,8 @@ GALV_INSTANCE_OK_FAST, GALV_INSTANCE_OK_INT64, GALV_INSTANCE_OK_FAST_WIDE = 0, 1
 GALV_INSTANCE_BAD_VALUE = -1
 
 EXPORTS = ("galv_dp_workspace_bytes", "galv_dp_create", "galv_dp_solve_batched",
-           "galv_dp_backtrack", "galv_dp_export_tables", "galv_dp_get_status",
+           "galv_dp_backtrack", "galv_dp_best_per_budget", "galv_dp_backtrack_queries",
+           "galv_dp_export_tables", "galv_dp_get_status",
            "galv_dp_destroy", "galv_dp_last_error")
 
 
@@ -59,6 +60,8 @@ def load_library() -> ctypes.CDLL:
         lib.galv_dp_create.argtypes = [ctypes.POINTER(Desc), vp, ctypes.c_size_t, ctypes.POINTER(vp)]
         lib.galv_dp_solve_batched.argtypes = [vp] * 9
         lib.galv_dp_backtrack.argtypes = [vp, vp, vp]
+        lib.galv_dp_best_per_budget.argtypes = [vp, vp, vp, vp]
+        lib.galv_dp_backtrack_queries.argtypes = [vp, i32, vp, vp, vp, vp, vp]
         lib.galv_dp_export_tables.argtypes = [vp, i32, vp, vp, vp]
         lib.galv_dp_get_status.argtypes = [vp, vp, vp]
         lib.galv_dp_destroy.argtypes = [vp]
@@ -124,6 +127,20 @@ def galv_dp_backtrack(h, plan, stream=None):
     _check(load_library().galv_dp_backtrack(h, _dev_ptr(plan, torch.int32), _stream_ptr(stream)))
 
 
+def galv_dp_best_per_budget(h, best_cost, best_last, stream=None):
+    _check(load_library().galv_dp_best_per_budget(
+        h, _dev_ptr(best_cost, torch.int64), _dev_ptr(best_last, torch.int32, allow_none=True),
+        _stream_ptr(stream)))
+
+
+def galv_dp_backtrack_queries(h, instance, budget, cost, plan, stream=None):
+    n = int(instance.numel())
+    _check(load_library().galv_dp_backtrack_queries(
+        h, n, _dev_ptr(instance, torch.int32, (n,)), _dev_ptr(budget, torch.int32, (n,)),
+        _dev_ptr(cost, torch.int64, allow_none=True), _dev_ptr(plan, torch.int32),
+        _stream_ptr(stream)))
+
+
 def galv_dp_export_tables(h, instance, C_last, bp, stream=None):
     _check(load_library().galv_dp_export_tables(
         h, int(instance), _dev_ptr(C_last, torch.int64),
@@ -169,6 +186,21 @@ class Solver:
     def backtrack(self, stream=None):
         galv_dp_backtrack(self.handle, self.plan, stream)
         return self.plan
+
+    def best_per_budget(self, stream=None):
+        """(best_cost[B][E_max+1], best_last[B][E_max+1]) for every budget column."""
+        cost = torch.empty((self.B, self.E_max + 1), dtype=torch.int64, device=self.device)
+        last = torch.empty((self.B, self.E_max + 1), dtype=torch.int32, device=self.device)
+        galv_dp_best_per_budget(self.handle, cost, last, stream)
+        return cost, last
+
+    def backtrack_queries(self, instance, budget, stream=None):
+        """Plans for (instance, budget) pairs given as int32 device tensors: (cost[Q], plan[Q][L])."""
+        q = int(instance.numel())
+        cost = torch.empty(q, dtype=torch.int64, device=self.device)
+        plan = torch.empty((q, self.L), dtype=torch.int32, device=self.device)
+        galv_dp_backtrack_queries(self.handle, instance, budget, cost, plan, stream)
+        return cost, plan
 
     def export_tables(self, instance, want_bp=True, stream=None):
         C_last = torch.empty((self.E_max + 1, self.S), dtype=torch.int64, device=self.device)

@@ -640,17 +640,13 @@ __global__ __launch_bounds__(kThreads) void final_kernel(Layout a, int64_t *best
     }
 }
 
-// One thread per instance: L dependent loads through the un-shifted argmin table.
-__global__ __launch_bounds__(kWave) void backtrack_kernel(Layout a, int32_t *plan) {
-    const int b = blockIdx.x * kWave + threadIdx.x;
-    if (b >= a.B) return;
-    int32_t *out = plan + (int64_t)b * a.L;
-    int s = a.last[b];
+// Walk the un-shifted argmin table of instance b from (L-1, e, s) down to layer 0:
+// L dependent loads.  Writes the plan, or all -1 when s < 0.
+__device__ __forceinline__ void walk_plan(const Layout &a, int b, int64_t e, int s, int32_t *out) {
     if (s < 0) {
         for (int l = 0; l < a.L; ++l) out[l] = -1;
         return;
     }
-    int64_t e = a.budget[b];
     for (int l = a.L - 1; l >= 1; --l) {
         out[l] = s;
         e -= a.m[((int64_t)b * a.L + l) * a.S + s];
@@ -667,6 +663,59 @@ __global__ __launch_bounds__(kWave) void backtrack_kernel(Layout a, int32_t *pla
         }
     }
     out[0] = s;
+}
+
+// One thread per instance, from the full budget and the stored best last strategy.
+__global__ __launch_bounds__(kWave) void backtrack_kernel(Layout a, int32_t *plan) {
+    const int b = blockIdx.x * kWave + threadIdx.x;
+    if (b >= a.B) return;
+    walk_plan(a, b, a.budget[b], a.last[b], plan + (int64_t)b * a.L);
+}
+
+// min_s C[L-1][e][s] and the lowest minimising s for one (instance, budget column).
+__device__ __forceinline__ void best_at(const Layout &a, int b, int st, int64_t e, int64_t &opt,
+                                        int32_t &last) {
+    opt = kInf;
+    last = -1;
+    for (int s = 0; s < a.S; ++s) {
+        const int64_t v = last_layer_cost(a, b, st, e, s);
+        if (v < opt) {
+            opt = v;
+            last = s;
+        }
+    }
+}
+
+// The optimum of every budget column.  Grid: (column tiles, B).
+__global__ __launch_bounds__(kThreads) void best_per_budget_kernel(Layout a, int64_t *best_cost,
+                                                                   int32_t *best_last) {
+    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e > a.E_max) return;
+    const int b = blockIdx.y;
+    const int st = a.status[b];
+    int64_t opt = kInf;
+    int32_t last = -1;
+    if (st >= 0 && e <= a.budget[b]) best_at(a, b, st, e, opt, last);
+    best_cost[(int64_t)b * (a.E_max + 1) + e] = opt;
+    if (best_last) best_last[(int64_t)b * (a.E_max + 1) + e] = last;
+}
+
+// One thread per (instance, budget) query: final minimum at that column, then the walk.
+__global__ __launch_bounds__(kWave) void backtrack_queries_kernel(Layout a, int n, const int32_t *inst,
+                                                                  const int32_t *budgets,
+                                                                  int64_t *cost, int32_t *plan) {
+    const int q = blockIdx.x * kWave + threadIdx.x;
+    if (q >= n) return;
+    const int b = inst[q];
+    const int64_t e = budgets[q];
+    int64_t opt = kInf;
+    int32_t last = -1;
+    if (b >= 0 && b < a.B) {
+        const int st = a.status[b];
+        if (st >= 0 && e >= 0 && e <= a.budget[b]) best_at(a, b, st, e, opt, last);
+    }
+    if (cost) cost[q] = opt;
+    walk_plan(a, b < 0 || b >= a.B ? 0 : b, e, last, plan + (int64_t)q * a.L);
 }
 
 // Canonical-order tables of one instance.  Grid: (e tiles, L + 1); row L of the
@@ -909,6 +958,35 @@ galv_status_t galv_dp_backtrack(galv_dp_t *h, int32_t *plan_dev, void *stream) {
     const Layout &a = h->lay;
     backtrack_kernel<<<(a.B + kWave - 1) / kWave, kWave, 0, static_cast<hipStream_t>(stream)>>>(
         a, plan_dev);
+    HIP_TRY(hipGetLastError());
+    return GALV_OK;
+}
+
+galv_status_t galv_dp_best_per_budget(galv_dp_t *h, int64_t *best_cost_dev, int32_t *best_last_dev,
+                                      void *stream) {
+    if (!h) return fail(GALV_ERR_INVALID_ARG, "handle is NULL");
+    if (!best_cost_dev) return fail(GALV_ERR_INVALID_ARG, "best_cost_dev is NULL");
+    if (!h->solved) return fail(GALV_ERR_STATE, "best_per_budget before a successful solve");
+    const Layout &a = h->lay;
+    const dim3 grid((unsigned)((a.E_max + kThreads) / kThreads), a.B);
+    best_per_budget_kernel<<<grid, kThreads, 0, static_cast<hipStream_t>(stream)>>>(a, best_cost_dev,
+                                                                                  best_last_dev);
+    HIP_TRY(hipGetLastError());
+    return GALV_OK;
+}
+
+galv_status_t galv_dp_backtrack_queries(galv_dp_t *h, int32_t n_queries, const int32_t *instance_dev,
+                                        const int32_t *budget_dev, int64_t *cost_dev,
+                                        int32_t *plan_dev, void *stream) {
+    if (!h) return fail(GALV_ERR_INVALID_ARG, "handle is NULL");
+    if (n_queries < 0) return fail(GALV_ERR_INVALID_ARG, "n_queries %d is negative", n_queries);
+    if (n_queries == 0) return GALV_OK;
+    if (!instance_dev || !budget_dev || !plan_dev)
+        return fail(GALV_ERR_INVALID_ARG, "a required device pointer is NULL");
+    if (!h->solved) return fail(GALV_ERR_STATE, "backtrack_queries before a successful solve");
+    backtrack_queries_kernel<<<(n_queries + kWave - 1) / kWave, kWave, 0,
+                               static_cast<hipStream_t>(stream)>>>(h->lay, n_queries, instance_dev,
+                                                                   budget_dev, cost_dev, plan_dev);
     HIP_TRY(hipGetLastError());
     return GALV_OK;
 }

@@ -72,4 +72,6 @@ def test_null_handle_calls(lib):
     assert lib.galv_dp_backtrack(None, None, None) == binding.GALV_ERR_INVALID_ARG
     assert lib.galv_dp_export_tables(None, 0, None, None, None) == binding.GALV_ERR_INVALID_ARG
     assert lib.galv_dp_get_status(None, None, None) == binding.GALV_ERR_INVALID_ARG
+    assert lib.galv_dp_best_per_budget(None, None, None, None) == binding.GALV_ERR_INVALID_ARG
+    assert lib.galv_dp_backtrack_queries(None, 1, None, None, None, None, None) == binding.GALV_ERR_INVALID_ARG
     assert lib.galv_dp_destroy(None) == binding.GALV_OK
