@@ -157,6 +157,41 @@ galv_status_t galv_dp_export_tables(galv_dp_t *h, int32_t instance, int64_t *C_l
 /* Copy the per-instance status codes of the last solve: status_dev [B] int32. */
 galv_status_t galv_dp_get_status(galv_dp_t *h, int32_t *status_dev, void *stream);
 
+/*
+ * Outer loop of Algorithm 1 ("Optimization Workflow" of section 3.3) over a window of
+ * candidate batch sizes, on the device, from stage optima that galv_dp_solve_batched wrote.
+ * For batch size ib and pipeline degree P = pp_degree[ip] the time cost is the sum of its P
+ * stage optima (GALV_INF if any stage has no plan that fits); C_opt is the minimum over the
+ * degrees (lowest ip on ties); batch sizes are scanned in the order given and the state keeps
+ * the one with the largest throughput batch_size / C_opt (compared exactly as integers; the
+ * earlier one on ties) until the first batch size whose C_opt is GALV_INF (Out-Of-Memory),
+ * where the scan stops for good.
+ *   pp_degree      [n_pp]  HOST int32  pipeline degrees, 1 <= n_pp <= 16
+ *   stage_cost_dev         int64  for ip = 0..n_pp-1 in turn a block [n_batch][pp_degree[ip]]
+ *                                 of stage optima (the best_cost outputs of one solve per degree)
+ *   batch_size_dev [n_batch] int64  the batch sizes B > 0 of this window
+ *   batch_index_base       added to the window-local index when recording the best batch size
+ *   first_window           non-zero: start from an empty state (throughput 0); zero: continue
+ *                          from *state_dev as an earlier call left it
+ *   c_p_dev  [n_batch][n_pp] out int64  the time costs C_P
+ *   state_dev  in/out      see galv_alg1_state_t
+ * Precondition: each sum of stage optima stays below 2^62 (a larger sum reads as GALV_INF).
+ * Enqueues one small kernel on `stream`; never synchronises or allocates.
+ */
+typedef struct {
+    int64_t batch_size;  /* B of the best throughput so far; 0 while there is none          */
+    int64_t cost;        /* its C_opt; throughput = batch_size / cost                        */
+    int32_t pp_index;    /* index into pp_degree of the degree that gave C_opt; -1 if none   */
+    int32_t batch_index; /* batch_index_base + window index of that batch size; -1 if none   */
+    int32_t stopped;     /* 1 once a batch size fitted under no pipeline degree              */
+    int32_t n_explored;  /* batch sizes examined before stopping                             */
+} galv_alg1_state_t;
+
+galv_status_t galv_alg1_reduce(int32_t n_batch, int32_t n_pp, const int32_t *pp_degree,
+                               const int64_t *stage_cost_dev, const int64_t *batch_size_dev,
+                               int32_t batch_index_base, int32_t first_window, int64_t *c_p_dev,
+                               galv_alg1_state_t *state_dev, void *stream);
+
 /* Free the handle (host memory only; the workspace stays the caller's). NULL is allowed. */
 galv_status_t galv_dp_destroy(galv_dp_t *h);
 

@@ -27,7 +27,7 @@ GALV_INSTANCE_BAD_VALUE = -1
 
 EXPORTS = ("galv_dp_workspace_bytes", "galv_dp_create", "galv_dp_solve_batched",
            "galv_dp_backtrack", "galv_dp_best_per_budget", "galv_dp_backtrack_queries",
-           "galv_dp_export_tables", "galv_dp_get_status",
+           "galv_dp_export_tables", "galv_dp_get_status", "galv_alg1_reduce",
            "galv_dp_destroy", "galv_dp_last_error")
 
 
@@ -64,6 +64,7 @@ def load_library() -> ctypes.CDLL:
         lib.galv_dp_backtrack_queries.argtypes = [vp, i32, vp, vp, vp, vp, vp]
         lib.galv_dp_export_tables.argtypes = [vp, i32, vp, vp, vp]
         lib.galv_dp_get_status.argtypes = [vp, vp, vp]
+        lib.galv_alg1_reduce.argtypes = [i32, i32, ctypes.POINTER(i32), vp, vp, i32, i32, vp, vp, vp]
         lib.galv_dp_destroy.argtypes = [vp]
         for name in EXPORTS[:-1]:
             getattr(lib, name).restype = ctypes.c_int
@@ -149,6 +150,21 @@ def galv_dp_export_tables(h, instance, C_last, bp, stream=None):
 
 def galv_dp_get_status(h, status, stream=None):
     _check(load_library().galv_dp_get_status(h, _dev_ptr(status, torch.int32), _stream_ptr(stream)))
+
+
+# galv_alg1_state_t as six int32 words would misread the int64 fields; it is moved as raw bytes.
+ALG1_STATE_BYTES = 32
+
+
+def galv_alg1_reduce(pp_degree, stage_cost, batch_size, batch_index_base, first_window, c_p, state,
+                     stream=None):
+    n_batch, n_pp = int(batch_size.numel()), len(pp_degree)
+    arr = (ctypes.c_int32 * n_pp)(*[int(p) for p in pp_degree])
+    _dev_ptr(stage_cost, torch.int64, (n_batch * sum(int(p) for p in pp_degree),))
+    _check(load_library().galv_alg1_reduce(
+        n_batch, n_pp, arr, _dev_ptr(stage_cost, torch.int64), _dev_ptr(batch_size, torch.int64),
+        int(batch_index_base), int(bool(first_window)), _dev_ptr(c_p, torch.int64, (n_batch, n_pp)),
+        _dev_ptr(state, torch.uint8, (ALG1_STATE_BYTES,)), _stream_ptr(stream)))
 
 
 def galv_dp_destroy(h):

@@ -54,6 +54,7 @@ constexpr int kThreads = 256;          // workgroup = 4 wavefronts of 64
 constexpr int kWave = 64;
 constexpr int kEAlign = 1024;          // budget columns are padded to this
 constexpr int kMaxS = 1024;
+constexpr int kMaxPp = 16;            // pipeline degrees per reduce call
 #ifndef GALV_DEPTH
 #define GALV_DEPTH 2
 #endif
@@ -764,6 +765,63 @@ __global__ __launch_bounds__(kThreads) void export_kernel(Layout a, int b, int64
 #define GALV_V5 16, 2, 2, 6
 #endif
 
+// ---------------------------------------------------------------------------------------------
+// Outer loop of Algorithm 1 over a window of batch sizes: per (batch size, pipeline degree) the
+// stage optima are summed, the minimum over pipeline degrees is C_opt, and the scan over batch
+// sizes keeps the largest B / C_opt until the first batch size that fits under no degree.
+// One workgroup: the sums in parallel, the scan by one lane (it is a dependent chain).
+struct PpList {
+    int n;
+    int degree[kMaxPp];
+};
+
+__global__ __launch_bounds__(kThreads) void alg1_reduce_kernel(
+    int n_batch, PpList pp, const int64_t *__restrict__ stage_cost,
+    const int64_t *__restrict__ batch_size, int batch_index_base, int first_window,
+    int64_t *__restrict__ c_p, galv_alg1_state_t *__restrict__ state) {
+    for (int i = threadIdx.x; i < n_batch * pp.n; i += kThreads) {
+        const int ib = i / pp.n, ip = i % pp.n;
+        size_t off = 0;
+        for (int j = 0; j < ip; ++j) off += (size_t)n_batch * pp.degree[j];
+        const int64_t *x = stage_cost + off + (size_t)ib * pp.degree[ip];
+        int64_t acc = 0;
+        for (int st = 0; st < pp.degree[ip]; ++st) {
+            const int64_t v = x[st];
+            acc = (acc >= kInf || v < 0 || v >= kInf - acc) ? kInf : acc + v;
+        }
+        c_p[i] = acc;
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    galv_alg1_state_t s;
+    if (first_window) {
+        s.batch_size = 0; s.cost = 1; s.pp_index = -1; s.batch_index = -1;
+        s.stopped = 0; s.n_explored = 0;
+    } else {
+        s = *state;
+    }
+    for (int ib = 0; ib < n_batch && !s.stopped; ++ib) {
+        int64_t c_opt = kInf;
+        int arg = -1;
+        for (int ip = 0; ip < pp.n; ++ip) {
+            const int64_t v = c_p[(size_t)ib * pp.n + ip];
+            if (v < c_opt) { c_opt = v; arg = ip; }
+        }
+        if (arg < 0) { s.stopped = 1; break; }          // Out-Of-Memory under every degree
+        ++s.n_explored;
+        const int64_t bsz = batch_size[ib];
+        // bsz / c_opt > s.batch_size / s.cost, compared exactly as cross products
+        const unsigned __int128 lhs = (unsigned __int128)(uint64_t)bsz * (uint64_t)s.cost;
+        const unsigned __int128 rhs = (unsigned __int128)(uint64_t)s.batch_size * (uint64_t)c_opt;
+        if (bsz > 0 && lhs > rhs) {
+            s.batch_size = bsz; s.cost = c_opt; s.pp_index = arg;
+            s.batch_index = batch_index_base + ib;
+        }
+    }
+    *state = s;
+}
+
+
 using SweepFn = void (*)(Layout, int);
 struct VariantEntry {
     Variant v;
@@ -1013,6 +1071,32 @@ galv_status_t galv_dp_get_status(galv_dp_t *h, int32_t *status_dev, void *stream
     if (!h->solved) return fail(GALV_ERR_STATE, "status before a successful solve");
     HIP_TRY(hipMemcpyAsync(status_dev, h->lay.status, (size_t)h->lay.B * sizeof(int32_t),
                            hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)));
+    return GALV_OK;
+}
+
+galv_status_t galv_alg1_reduce(int32_t n_batch, int32_t n_pp, const int32_t *pp_degree,
+                               const int64_t *stage_cost_dev, const int64_t *batch_size_dev,
+                               int32_t batch_index_base, int32_t first_window, int64_t *c_p_dev,
+                               galv_alg1_state_t *state_dev, void *stream) {
+    if (n_batch < 1 || n_batch > (1 << 20))
+        return fail(GALV_ERR_INVALID_ARG, "n_batch %d out of range [1, 2^20]", n_batch);
+    if (n_pp < 1 || n_pp > kMaxPp)
+        return fail(GALV_ERR_INVALID_ARG, "n_pp %d out of range [1, %d]", n_pp, kMaxPp);
+    if (!pp_degree || !stage_cost_dev || !batch_size_dev || !c_p_dev || !state_dev)
+        return fail(GALV_ERR_INVALID_ARG, "a required pointer is NULL");
+    PpList pp;
+    pp.n = n_pp;
+    for (int i = 0; i < kMaxPp; ++i) pp.degree[i] = 0;
+    for (int i = 0; i < n_pp; ++i) {
+        if (pp_degree[i] < 1 || pp_degree[i] > (1 << 16))
+            return fail(GALV_ERR_INVALID_ARG, "pp_degree[%d] = %d out of range [1, 65536]", i,
+                        pp_degree[i]);
+        pp.degree[i] = pp_degree[i];
+    }
+    alg1_reduce_kernel<<<1, kThreads, 0, static_cast<hipStream_t>(stream)>>>(
+        n_batch, pp, stage_cost_dev, batch_size_dev, batch_index_base, first_window, c_p_dev,
+        state_dev);
+    HIP_TRY(hipGetLastError());
     return GALV_OK;
 }
 

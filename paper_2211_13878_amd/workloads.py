@@ -207,3 +207,42 @@ def random_workload(seed: int, B: int, L: int, S: int, E_max: int, *, nR: int = 
     if budgets is None:
         budgets = rng.integers(0, E_max + 1, size=B)
     return _stack(name, L, S, E_max, nR, inst, budgets)
+
+
+class Alg1Model:
+    """Seeded stand-in for the paper's cost estimator (section 3.4), as Algorithm 1 consumes it.
+
+    For a batch size B, a pipeline degree P and a contiguous range of layers it
+    returns the tables of one stage's search: c(l, s), m(l, s) and R(s', s) over
+    the S_P strategies of a group of N / P devices.  Values are affine in B with
+    drawn coefficients: time grows with B, so does memory (activations), faster
+    strategies need more memory, a layer needs P times more memory per device on
+    a group that is P times smaller, and each degree has its own speed factor.  `n_strategies` maps each P to S_P (the caller counts
+    the decision trees; this class only draws numbers).
+    """
+
+    def __init__(self, seed: int, n_layers: int, n_devices: int, n_strategies: dict,
+                 time_scale: int = 400, mem_fixed: int = 20, mem_per_sample: int = 4):
+        self.n_layers, self.n_devices = n_layers, n_devices
+        self.n_strategies = dict(n_strategies)
+        rng = np.random.default_rng(seed)
+        self._coef = {}
+        for pp in sorted(self.n_strategies):
+            S = self.n_strategies[pp]
+            speed = rng.uniform(1.0, 4.0, size=(n_layers, S))
+            f_pp = rng.uniform(0.7, 1.3)
+            alpha = np.rint(time_scale * f_pp / speed * rng.uniform(0.9, 1.1, size=(n_layers, S)))
+            beta = rng.integers(0, 5 * time_scale, size=(n_layers, S))
+            mu = np.rint(mem_fixed * pp * speed)
+            nu = np.rint(mem_per_sample * pp * speed)
+            rho = rng.integers(0, time_scale // 2, size=(S, S))
+            np.fill_diagonal(rho, 0)
+            self._coef[pp] = (alpha.astype(np.int64), beta.astype(np.int64), mu.astype(np.int64),
+                              nu.astype(np.int64), rho.astype(np.int64))
+
+    def stage_tables(self, batch: int, pp: int, lo: int, hi: int):
+        """(c[hi-lo][S] int64, m[hi-lo][S] int32, R[S][S] int64) of layers lo..hi-1."""
+        alpha, beta, mu, nu, rho = self._coef[pp]
+        c = alpha[lo:hi] * batch + beta[lo:hi]
+        m = np.minimum(mu[lo:hi] + nu[lo:hi] * batch, np.iinfo(np.int32).max).astype(np.int32)
+        return np.ascontiguousarray(c), np.ascontiguousarray(m), np.ascontiguousarray(rho * batch)

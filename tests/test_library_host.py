@@ -22,7 +22,7 @@ def lib():
 
 def test_exports_match_header(lib):
     header = open(os.path.join(ROOT, "include", "galv_dp.h")).read()
-    declared = set(re.findall(r"\b(galv_dp_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(galv_(?:dp|alg1)_[a-z0-9_]+)\s*\(", header))
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
@@ -75,3 +75,16 @@ def test_null_handle_calls(lib):
     assert lib.galv_dp_best_per_budget(None, None, None, None) == binding.GALV_ERR_INVALID_ARG
     assert lib.galv_dp_backtrack_queries(None, 1, None, None, None, None, None) == binding.GALV_ERR_INVALID_ARG
     assert lib.galv_dp_destroy(None) == binding.GALV_OK
+
+
+def test_alg1_reduce_rejects_bad_host_arguments(lib):
+    deg = (ctypes.c_int32 * 2)(1, 2)
+    one = ctypes.c_void_p(256)          # never dereferenced: every call below fails before a launch
+    assert lib.galv_alg1_reduce(0, 2, deg, one, one, 0, 1, one, one, None) == binding.GALV_ERR_INVALID_ARG
+    assert lib.galv_alg1_reduce(1, 0, deg, one, one, 0, 1, one, one, None) == binding.GALV_ERR_INVALID_ARG
+    assert lib.galv_alg1_reduce(1, 17, deg, one, one, 0, 1, one, one, None) == binding.GALV_ERR_INVALID_ARG
+    assert lib.galv_alg1_reduce(1, 2, None, one, one, 0, 1, one, one, None) == binding.GALV_ERR_INVALID_ARG
+    assert lib.galv_alg1_reduce(1, 2, deg, None, one, 0, 1, one, one, None) == binding.GALV_ERR_INVALID_ARG
+    bad = (ctypes.c_int32 * 2)(1, 0)
+    assert lib.galv_alg1_reduce(1, 2, bad, one, one, 0, 1, one, one, None) == binding.GALV_ERR_INVALID_ARG
+    assert "pp_degree" in binding.galv_dp_last_error()
