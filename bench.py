@@ -69,6 +69,10 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload index 0..4 (default 3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--force-int64", action="store_true", help="time the general integer kernels")
+    ap.add_argument("--bp-u8", action="store_true",
+                    help="store back-pointers in one byte (GALV_DP_BP_U8): 9 instead of 12 B per state")
+    ap.add_argument("--streams", type=int, default=0,
+                    help="internal streams the layer sweeps are spread over (0 = library's choice, 1 = none)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic: 1 GiB read, "
                          "1 GiB written) so that rocprofv3 FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -87,14 +91,10 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     w = workloads.config(args.config)
-    flags = binding.GALV_DP_FORCE_INT64 if args.force_int64 else 0
-    sol = binding.Solver(w.B, w.L, w.S, w.E_max, w.nR, flags)
+    base_flags = ((binding.GALV_DP_FORCE_INT64 if args.force_int64 else 0) |
+                  (binding.GALV_DP_BP_U8 if args.bp_u8 else 0))
     dev = binding.upload(w)
     torch.cuda.synchronize()
-
-    def step():
-        sol.solve(*dev)
-        sol.backtrack()
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
@@ -103,37 +103,58 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    # Events sit on torch's current stream, which is the stream the binding hands
-    # to the library, so they bracket exactly the library's launches.
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-          for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for a, b in ev:
-        a.record()
-        sol.solve(*dev)
-        b.record()
-        sol.backtrack()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    solve_ms = sorted(a.elapsed_time(b) for a, b in ev)
-    status = sol.status().cpu().numpy()
-    cost = sol.best_cost.cpu().numpy()
 
-    ms_per_step = wall * 1e3 / args.steps
+    def timed(flags, steps, warmup):
+        """K steps (solve + backtrack) on a fresh handle: wall ms per step, solve ms per step."""
+        sol = binding.Solver(w.B, w.L, w.S, w.E_max, w.nR, flags)
+        for _ in range(warmup):
+            sol.solve(*dev)
+            sol.backtrack()
+        torch.cuda.synchronize()
+        # Events sit on torch's current stream, which is the stream the binding hands to the
+        # library; the library joins its internal streams back into it before the final
+        # minimum, so the events bracket all of a solve's launches.
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(steps)]
+        t0 = time.perf_counter()
+        for a, b in ev:
+            a.record()
+            sol.solve(*dev)
+            b.record()
+            sol.backtrack()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        solve_ms = sorted(a.elapsed_time(b) for a, b in ev)
+        status = sol.status().cpu().numpy()
+        cost = sol.best_cost.cpu().numpy()
+        sol.close()
+        del sol
+        torch.cuda.empty_cache()
+        return wall * 1e3 / steps, solve_ms, status, cost
+
     nominal = w.nominal_cell_updates()
     exact = w.exact_candidates()
     states = w.n_states()
-    n_launch = max(1, w.L - 1)
-    sweep_ms = sum(solve_ms) / len(solve_ms) / n_launch      # average sweep launch (upper bound:
-    #                                                           includes prep/init/final, < 1 %)
+    n_layer_steps = max(1, w.L - 1)
     ops = OPS_PER_CANDIDATE if not args.force_int64 else 6
-    achieved = exact / n_launch * ops / (sweep_ms * 1e-3) / 1e12
-    per_state = [BYTES_PER_STATE.get(int(st), 0) for st in status]
+
+    def alu(solve_ms):
+        """Sweep lane-ops per layer step over its duration (prep / init / final are < 1 % and
+        counted into the duration, so this is a lower bound)."""
+        layer_ms = sum(solve_ms) / len(solve_ms) / n_layer_steps
+        achieved = exact / n_layer_steps * ops / (layer_ms * 1e-3) / 1e12
+        return layer_ms, achieved
+
+    ms_per_step, solve_ms, status, cost = timed(base_flags | binding.GALV_DP_STREAMS(args.streams),
+                                                args.steps, args.warmup)
+    sweep_ms, achieved = alu(solve_ms)
+    per_state = [BYTES_PER_STATE.get(int(st), 0) - (3 if args.bp_u8 else 0) for st in status]
     hbm_bytes = sum(p * (int(e) + 1) * w.S for p, e in zip(per_state, w.budget))   # per layer
     hbm_gbs = hbm_bytes / (sweep_ms * 1e-3) / 1e9
+    # The same kernel with every layer as ONE launch on one stream: the per-launch figure that
+    # a kernel trace shows directly (with several streams the launches overlap in time).
+    _, solve_ms_1, _, _ = timed(base_flags | binding.GALV_DP_STREAMS(1), max(2, args.steps // 2), 1)
+    launch_ms_1, achieved_1 = alu(solve_ms_1)
 
     out = {
         "metric": "dp_cell_updates_per_sec",
@@ -146,6 +167,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"config {args.config} '{w.name}': B={w.B} L={w.L} S={w.S} "
                                f"E_max={w.E_max} budgets {int(w.budget.min())}..{int(w.budget.max())}",
+                   "back_pointer_bytes": 1 if args.bp_u8 else 4,
+                   "internal_streams": "auto" if args.streams == 0 else args.streams,
                    "cell_updates_per_batch": nominal, "exact_candidates_per_batch": exact,
                    "table_states_per_batch": states},
         "searches_per_sec": w.B / (ms_per_step * 1e-3),
@@ -156,12 +179,23 @@ def main():
         "roofline": {"bound": "alu", "kernel": "sweep_kernel", "achieved": achieved,
                      "peak": VALU_PEAK_TLANEOPS, "unit": "Tlane-op/s",
                      "frac": achieved / VALU_PEAK_TLANEOPS,
-                     "traffic": None if args.force_int64 else MEASURED_TRAFFIC_BYTES.get(args.config),
+                     "traffic": None if (args.force_int64 or args.bp_u8) else MEASURED_TRAFFIC_BYTES.get(args.config),
                      "launch_ms": sweep_ms, "lane_ops_per_candidate": ops,
+                     "note": "per layer step of the whole batch; with internal streams a layer step is "
+                             "several overlapping launches, so single_stream gives the one-launch-per-layer "
+                             "figure that a kernel trace shows directly",
+                     "single_stream": {"achieved": achieved_1, "frac": achieved_1 / VALU_PEAK_TLANEOPS,
+                                       "launch_ms": launch_ms_1},
                      "hbm": {"achieved": hbm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                              "frac": hbm_gbs / HBM_PEAK_GBS, "bytes_per_launch": hbm_bytes,
                              "bytes_per_state": max(per_state)}},
     }
+    if not (args.bp_u8 or args.force_int64) and w.S <= 255:
+        # NEXT-step variant, same results: one-byte back-pointers (9 instead of 12 B per state)
+        ms_u8, _, _, cost_u8 = timed(binding.GALV_DP_BP_U8 | binding.GALV_DP_STREAMS(args.streams),
+                                     max(2, args.steps // 2), 1)
+        assert (cost_u8 == cost).all()
+        out["variant_bp_u8"] = {"ms_per_step": ms_u8, "value": nominal / (ms_u8 * 1e-3)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

@@ -24,8 +24,13 @@
  *  - The caller owns all device buffers, including the workspace, and keeps the
  *    inputs alive and unchanged until the stream has passed the calls that read
  *    them (m_dev and budget_dev until the last backtrack / export of that solve).
- *  - solve / backtrack / export only enqueue work on `stream`; they never
- *    synchronise and never allocate.  galv_dp_create touches no device memory.
+ *  - solve / backtrack / export only enqueue work; they never synchronise the host and
+ *    never allocate.  Everything is ordered after the work already in `stream` and
+ *    before whatever is enqueued in `stream` afterwards.  Instances are independent,
+ *    so a solve may spread their layer sweeps over internal streams of the handle
+ *    (forked from and joined back into `stream` with events; see GALV_DP_STREAMS),
+ *    which lets sweeps of different instances overlap across layer boundaries.
+ *    galv_dp_create touches no device memory (it may create those streams).
  *  - Errors in host-visible arguments are returned as codes (never exceptions,
  *    never abort); galv_dp_last_error() gives a thread-local message.
  *  - Input VALUES live on the device and cannot be checked synchronously: a
@@ -71,6 +76,14 @@ typedef struct {
 /* flags */
 #define GALV_DP_FORCE_INT64 1u /* always use the general 64-bit integer kernels, even when
                                   an instance's values would allow the faster exact path */
+#define GALV_DP_BP_U8 2u       /* keep back-pointers in one byte instead of four (internal
+                                  storage only: results are identical); needs n_strategies <= 255.
+                                  Shrinks the largest table of the workspace and the dominant
+                                  HBM write of the sweep by 4x */
+
+#define GALV_DP_STREAMS_SHIFT 8 /* bits 8..12: how many internal streams the layer sweeps are   */
+#define GALV_DP_STREAMS_MASK 0x1f00u /* spread over; 0 = chosen from the shape, 1 = none, at most 16 */
+#define GALV_DP_STREAMS(n) ((uint32_t)(n) << GALV_DP_STREAMS_SHIFT)
 
 /* Per-instance status codes written by solve (see galv_dp_get_status). */
 #define GALV_INSTANCE_OK_FAST 0      /* packed-key kernels, costs stored in 32 bits (all plan

@@ -54,6 +54,7 @@ constexpr int kThreads = 256;          // workgroup = 4 wavefronts of 64
 constexpr int kWave = 64;
 constexpr int kEAlign = 1024;          // budget columns are padded to this
 constexpr int kMaxS = 1024;
+constexpr int kMaxSide = 16;          // internal streams per handle
 constexpr int kMaxPp = 16;            // pipeline degrees per reduce call
 #ifndef GALV_DEPTH
 #define GALV_DEPTH 2
@@ -99,7 +100,9 @@ struct Layout {
     int64_t row;          // cells per cost row: lead + padded columns (8 bytes reserved each)
     int64_t e_pad;        // padded budget columns (multiple of kEAlign)
     char *U[2];           // rolling cost rows   [B][S_pad][row] of 8-byte slots
-    int32_t *bp;          // argmin, un-shifted  [B][L-1][S][e_pad]
+    void *bp;             // argmin, un-shifted  [B][L-1][S][e_pad] of int32, or of uint8 (0xFF = none)
+    int32_t bp_u8;        // 1: one-byte back-pointers
+    int32_t b_off, b_step; // a sweep launch covers instances b_off + z * b_step (dealt over streams)
     double *Rk;           // R * 2^k + s'        [B][nR][S][S_pad] (+inf in padded columns)
     uint64_t *ck;         // per-mode c(l,s)     [B][L][S_pad]
     uint64_t *vlist;      // usable strategies of each layer, ascending: shift << 32 | s'  [B][L][S]
@@ -123,6 +126,21 @@ using ConstPtr = const T __attribute__((address_space(4))) *;
 template <class T>
 __device__ __forceinline__ ConstPtr<T> as_const(const T *p) {
     return (ConstPtr<T>)(uintptr_t)p;
+}
+
+// Back-pointer of un-shifted cell idx, whichever width the handle stores.
+__device__ __forceinline__ int32_t load_bp(const Layout &a, int64_t idx) {
+    if (a.bp_u8) {
+        const uint8_t v = static_cast<const uint8_t *>(a.bp)[idx];
+        return v == 0xFF ? -1 : (int32_t)v;
+    }
+    return static_cast<const int32_t *>(a.bp)[idx];
+}
+__device__ __forceinline__ void store_bp(const Layout &a, int64_t idx, int32_t v) {
+    if (a.bp_u8)
+        static_cast<uint8_t *>(a.bp)[idx] = (uint8_t)v;      // -1 becomes 0xFF
+    else
+        static_cast<int32_t *>(a.bp)[idx] = v;
 }
 
 // ------------------------------------------------------------- storage policies
@@ -368,7 +386,7 @@ __device__ __forceinline__ void sweep_int64(const Layout &a, int l, int b, int b
     const int64_t *Uprev = reinterpret_cast<const int64_t *>(a.U[(l - 1) & 1]) +
                            (int64_t)b * a.S_pad * a.row + a.lead;
     int64_t *Unew = reinterpret_cast<int64_t *>(a.U[l & 1]) + (int64_t)b * a.S_pad * a.row + a.lead;
-    int32_t *bp = a.bp + ((int64_t)b * (a.L - 1) + (l - 1)) * S * a.e_pad;
+    const int64_t bp0 = ((int64_t)b * (a.L - 1) + (l - 1)) * S * a.e_pad;
     const int32_t *mprev = a.m + ((int64_t)b * a.L + (l - 1)) * S;
     const int64_t *cl = a.c + ((int64_t)b * a.L + l) * S;
     const int r = a.r_idx ? a.r_idx[(int64_t)b * a.L + l] : 0;
@@ -405,7 +423,7 @@ __device__ __forceinline__ void sweep_int64(const Layout &a, int l, int b, int b
                 if (s0 + q < S) {
                     const bool dead = best[q] >= kInf;
                     Unew[(s0 + q) * a.row + e] = dead ? kInf : best[q] + cl[s0 + q];
-                    bp[(s0 + q) * a.e_pad + e] = dead ? -1 : arg[q];
+                    store_bp(a, bp0 + (s0 + q) * a.e_pad + e, dead ? -1 : arg[q]);
                 }
             }
         }
@@ -469,7 +487,7 @@ __device__ __forceinline__ void rgroup_await(RGroup<2> &g) {
 // Fast body.  Lane owns TE budget columns (64 apart) and TS strategy columns; per
 // usable s' it loads its TE shifted previous-layer cells once and reuses them for
 // all TS strategies, with the R keys as wave-uniform scalars.
-template <int TS, int TE, int NG, class Store>
+template <int TS, int TE, int NG, class Store, class BP>
 __device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int budget,
                                            int64_t tile_start) {
     using Cell = typename Store::Cell;
@@ -490,7 +508,7 @@ __device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int bu
                      (int64_t)b * a.S_pad * pitch + a.lead + e0;
     Cell *Un = reinterpret_cast<Cell *>(a.U[l & 1]) + ((int64_t)b * a.S_pad + s0) * pitch +
                a.lead + e0;
-    int32_t *bp = a.bp + (((int64_t)b * (a.L - 1) + (l - 1)) * S + s0) * a.e_pad + e0;
+    BP *bp = static_cast<BP *>(a.bp) + (((int64_t)b * (a.L - 1) + (l - 1)) * S + s0) * a.e_pad + e0;
     const int r = a.r_idx ? a.r_idx[(int64_t)b * a.L + l] : 0;
     const ConstPtr<double> Rk = as_const(a.Rk + ((int64_t)b * a.nR + r) * S * a.S_pad + s0);
     const ConstPtr<uint64_t> ck = as_const(a.ck + ((int64_t)b * a.L + l) * a.S_pad + s0);
@@ -576,24 +594,24 @@ __device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int bu
                 int32_t arg;
                 Store::finish(acc[s][j], cs, k, mask, cell, arg);
                 Un[(int64_t)s * pitch + j * kWave] = cell;
-                bp[(int64_t)s * a.e_pad + j * kWave] = arg;
+                bp[(int64_t)s * a.e_pad + j * kWave] = (BP)arg;      // -1 becomes 0xFF in one byte
             }
         }
     }
 }
 
-template <int TS, int TE, int NG, int WPE>
+template <int TS, int TE, int NG, int WPE, class BP>
 __global__ __launch_bounds__(kThreads, WPE) void sweep_kernel(Layout a, int l) {
-    const int b = blockIdx.z;
+    const int b = a.b_off + blockIdx.z * a.b_step;
     const int st = a.status[b];
     if (st < 0) return;
     const int budget = a.budget[b];
     const int64_t tile_start = (int64_t)blockIdx.x * a.tile_e;
     if (tile_start > budget) return;
     if (st == GALV_INSTANCE_OK_FAST) {
-        sweep_fast<TS, TE, NG, Narrow>(a, l, b, budget, tile_start);
+        sweep_fast<TS, TE, NG, Narrow, BP>(a, l, b, budget, tile_start);
     } else if (st == GALV_INSTANCE_OK_FAST_WIDE) {
-        sweep_fast<TS, TE, NG, Wide>(a, l, b, budget, tile_start);
+        sweep_fast<TS, TE, NG, Wide, BP>(a, l, b, budget, tile_start);
     } else {
         if (blockIdx.y == 0) sweep_int64<8>(a, l, b, budget, tile_start);
     }
@@ -657,7 +675,7 @@ __device__ __forceinline__ void walk_plan(const Layout &a, int b, int64_t e, int
             for (int q = 0; q < a.L; ++q) out[q] = -1;
             return;
         }
-        s = a.bp[(((int64_t)b * (a.L - 1) + (l - 1)) * a.S + s) * a.e_pad + e];
+        s = load_bp(a, (((int64_t)b * (a.L - 1) + (l - 1)) * a.S + s) * a.e_pad + e);
         if (s < 0 || s >= a.S) {
             for (int q = 0; q < a.L; ++q) out[q] = -1;
             return;
@@ -741,7 +759,7 @@ __global__ __launch_bounds__(kThreads) void export_kernel(Layout a, int b, int64
         if (live && l >= 1) {
             const int64_t shift = a.m[((int64_t)b * a.L + l) * a.S + s];
             if (shift <= e)
-                v = a.bp[(((int64_t)b * (a.L - 1) + (l - 1)) * a.S + s) * a.e_pad + (e - shift)];
+                v = load_bp(a, (((int64_t)b * (a.L - 1) + (l - 1)) * a.S + s) * a.e_pad + (e - shift));
         }
         dst[s] = v;
     }
@@ -825,12 +843,12 @@ __global__ __launch_bounds__(kThreads) void alg1_reduce_kernel(
 using SweepFn = void (*)(Layout, int);
 struct VariantEntry {
     Variant v;
-    SweepFn fn;
+    SweepFn fn, fn_u8;     // int32 and one-byte back-pointers
 };
 template <int TS, int TE, int NG, int WPE>
 VariantEntry variant_entry() {
     static_assert(NG == 1 || NG == 2 || NG == 4, "strategy groups per workgroup");
-    return {{TS, TE, NG}, sweep_kernel<TS, TE, NG, WPE>};
+    return {{TS, TE, NG}, sweep_kernel<TS, TE, NG, WPE, int32_t>, sweep_kernel<TS, TE, NG, WPE, uint8_t>};
 }
 
 const VariantEntry &pick_variant(int S) {
@@ -853,6 +871,9 @@ struct galv_dp {
     size_t ws_bytes;
     int groups_y;      // grid.y of the sweep
     bool solved;
+    int n_side;                    // > 1: the layer sweeps of disjoint instance ranges run on side streams
+    hipStream_t side[kMaxSide];
+    hipEvent_t fork, join[kMaxSide];
 };
 
 namespace {
@@ -876,7 +897,14 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     if (d->n_strategies > kMaxS)
         return fail(GALV_ERR_INVALID_ARG, "n_strategies %d exceeds the limit %d", d->n_strategies,
                     kMaxS);
-    if (d->flags & ~GALV_DP_FORCE_INT64) return fail(GALV_ERR_INVALID_ARG, "unknown flag bits");
+    if (d->flags & ~(GALV_DP_FORCE_INT64 | GALV_DP_BP_U8 | GALV_DP_STREAMS_MASK))
+        return fail(GALV_ERR_INVALID_ARG, "unknown flag bits");
+    if (((d->flags & GALV_DP_STREAMS_MASK) >> GALV_DP_STREAMS_SHIFT) > (uint32_t)kMaxSide)
+        return fail(GALV_ERR_INVALID_ARG, "at most %d internal streams", kMaxSide);
+    const bool u8 = (d->flags & GALV_DP_BP_U8) != 0;
+    if (u8 && d->n_strategies > 255)
+        return fail(GALV_ERR_INVALID_ARG, "one-byte back-pointers need n_strategies <= 255 (got %d)",
+                    d->n_strategies);
     if (d->n_instances > 65535)
         return fail(GALV_ERR_RANGE, "n_instances %d exceeds the grid limit 65535", d->n_instances);
     if (d->max_budget > (1 << 30))
@@ -885,13 +913,14 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     memset(p, 0, sizeof *p);
     const VariantEntry &ve = pick_variant(d->n_strategies);
     const Variant v = ve.v;
-    p->sweep = ve.fn;
+    p->sweep = u8 ? ve.fn_u8 : ve.fn;
     Layout &a = p->lay;
     a.B = d->n_instances;
     a.L = d->n_layers;
     a.S = d->n_strategies;
     a.E_max = d->max_budget;
     a.nR = d->n_transition;
+    a.bp_u8 = u8 ? 1 : 0;
     const int group = v.ts * v.ng;
     p->groups_y = (a.S + group - 1) / group;
     a.S_pad = p->groups_y * group;
@@ -907,7 +936,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
 
     // Sizes in long double first, to reject anything that would overflow size_t math.
     const long double approx = (long double)a.B * a.S_pad * a.row * 16 +
-                               (long double)a.B * (a.L - 1) * a.S * a.e_pad * 4 +
+                               (long double)a.B * (a.L - 1) * a.S * a.e_pad * (u8 ? 1 : 4) +
                                (long double)a.B * a.nR * a.S * a.S_pad * 8;
     if (approx > 1e15L) return fail(GALV_ERR_RANGE, "tables of %.3Lg bytes cannot be indexed", approx);
 
@@ -920,7 +949,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     const size_t u_bytes = (size_t)a.B * a.S_pad * a.row * 8;
     p->off_U[0] = take(u_bytes);
     p->off_U[1] = take(u_bytes);
-    p->off_bp = take((size_t)a.B * (a.L - 1) * a.S * a.e_pad * sizeof(int32_t));
+    p->off_bp = take((size_t)a.B * (a.L - 1) * a.S * a.e_pad * (u8 ? 1 : sizeof(int32_t)));
     // + slack: a group of R keys is fetched whole even when it straddles the row end
     p->off_Rk = take((size_t)a.B * a.nR * a.S * a.S_pad * sizeof(double) + 1024);
     p->off_ck = take((size_t)a.B * a.L * a.S_pad * sizeof(uint64_t));
@@ -968,11 +997,44 @@ galv_status_t galv_dp_create(const galv_dp_desc_t *desc, void *workspace_dev,
     h->ws_bytes = p.total;
     h->groups_y = p.groups_y;
     h->solved = false;
+    h->n_side = 0;
+    int n = (int)((desc->flags & GALV_DP_STREAMS_MASK) >> GALV_DP_STREAMS_SHIFT);
+    if (n == 0) {
+        // Automatic: enough streams to keep the chip busy across layer boundaries once a
+        // layer's sweep is long enough to pay for the extra launches.  Estimated from the
+        // shape at ~2e13 lane-operations/s.  Measured on MI355X: 5-7 and 10 streams gain
+        // 20-25 % on long sweeps, 2 gain ~15 % on mid-sized ones, multiples of 4 (the
+        // number of hardware queues) gain little, and short sweeps lose.
+        const double us = 2.0 * desc->n_instances * ((double)desc->max_budget + 1) *
+                          desc->n_strategies * desc->n_strategies / 2e13 * 1e6;
+        n = us < 20.0 ? 1 : (us < 150.0 ? 2 : 6);
+    }
+    if (n > desc->n_instances) n = desc->n_instances;
+    if (n > 1 && desc->n_layers > 1) {
+        hipError_t e = hipEventCreateWithFlags(&h->fork, hipEventDisableTiming);
+        const bool have_fork = e == hipSuccess;
+        int made_s = 0, made_e = 0;
+        for (int g = 0; g < n && e == hipSuccess; ++g) {
+            e = hipStreamCreateWithFlags(&h->side[g], hipStreamNonBlocking);   // default priority
+            if (e != hipSuccess) break;
+            ++made_s;
+            e = hipEventCreateWithFlags(&h->join[g], hipEventDisableTiming);
+            if (e == hipSuccess) ++made_e;
+        }
+        if (e != hipSuccess) {
+            for (int g = 0; g < made_s; ++g) (void)hipStreamDestroy(h->side[g]);
+            for (int g = 0; g < made_e; ++g) (void)hipEventDestroy(h->join[g]);
+            if (have_fork) (void)hipEventDestroy(h->fork);
+            delete h;
+            return fail(GALV_ERR_HIP, "creating internal streams failed: %s", hipGetErrorString(e));
+        }
+        h->n_side = n;
+    }
     char *ws = static_cast<char *>(workspace_dev);
     Layout &a = h->lay;
     a.U[0] = ws + p.off_U[0];
     a.U[1] = ws + p.off_U[1];
-    a.bp = reinterpret_cast<int32_t *>(ws + p.off_bp);
+    a.bp = ws + p.off_bp;
     a.Rk = reinterpret_cast<double *>(ws + p.off_Rk);
     a.ck = reinterpret_cast<uint64_t *>(ws + p.off_ck);
     a.vlist = reinterpret_cast<uint64_t *>(ws + p.off_vlist);
@@ -1001,8 +1063,29 @@ galv_status_t galv_dp_solve_batched(galv_dp_t *h, const int64_t *c_dev, const in
 
     prep_kernel<<<a.B, kThreads, 0, st>>>(a, h->desc.flags);
     init_kernel<<<dim3((unsigned)((a.row + kThreads - 1) / kThreads), a.S, a.B), kThreads, 0, st>>>(a);
-    const dim3 grid(a.n_tiles, h->groups_y, a.B);
-    for (int l = 1; l < a.L; ++l) h->sweep<<<grid, kThreads, 0, st>>>(a, l);
+    a.b_off = 0;
+    a.b_step = 1;
+    if (h->n_side <= 1 || a.L < 2) {
+        const dim3 grid(a.n_tiles, h->groups_y, a.B);
+        for (int l = 1; l < a.L; ++l) h->sweep<<<grid, kThreads, 0, st>>>(a, l);
+    } else {
+        // Instances are independent, so their layer chains need no common barrier: each
+        // side stream sweeps its own share of the instances (dealt round-robin, which balances
+        // unequal budgets) and the shares overlap freely.
+        HIP_TRY(hipEventRecord(h->fork, st));
+        for (int g = 0; g < h->n_side; ++g) {
+            const int count = (a.B - g + h->n_side - 1) / h->n_side;    // instances g, g + n, g + 2n, ...
+            if (count <= 0) continue;
+            HIP_TRY(hipStreamWaitEvent(h->side[g], h->fork, 0));
+            Layout ag = a;
+            ag.b_off = g;
+            ag.b_step = h->n_side;
+            const dim3 grid(a.n_tiles, h->groups_y, count);
+            for (int l = 1; l < a.L; ++l) h->sweep<<<grid, kThreads, 0, h->side[g]>>>(ag, l);
+            HIP_TRY(hipEventRecord(h->join[g], h->side[g]));
+            HIP_TRY(hipStreamWaitEvent(st, h->join[g], 0));
+        }
+    }
     final_kernel<<<a.B, kThreads, 0, st>>>(a, best_cost_dev, best_last_dev);
     HIP_TRY(hipGetLastError());
     h->solved = true;
@@ -1101,6 +1184,13 @@ galv_status_t galv_alg1_reduce(int32_t n_batch, int32_t n_pp, const int32_t *pp_
 }
 
 galv_status_t galv_dp_destroy(galv_dp_t *h) {
+    if (h && h->n_side > 1) {
+        for (int g = 0; g < h->n_side; ++g) {
+            (void)hipStreamDestroy(h->side[g]);
+            (void)hipEventDestroy(h->join[g]);
+        }
+        (void)hipEventDestroy(h->fork);
+    }
     delete h;
     return GALV_OK;
 }

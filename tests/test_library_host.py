@@ -88,3 +88,14 @@ def test_alg1_reduce_rejects_bad_host_arguments(lib):
     bad = (ctypes.c_int32 * 2)(1, 0)
     assert lib.galv_alg1_reduce(1, 2, bad, one, one, 0, 1, one, one, None) == binding.GALV_ERR_INVALID_ARG
     assert "pp_degree" in binding.galv_dp_last_error()
+
+
+def test_one_byte_back_pointers_need_few_strategies(lib):
+    n = ctypes.c_size_t(0)
+    ok = binding.make_desc(1, 4, 255, 256, flags=binding.GALV_DP_BP_U8)
+    assert lib.galv_dp_workspace_bytes(ctypes.byref(ok), ctypes.byref(n)) == binding.GALV_OK
+    bad = binding.make_desc(1, 4, 256, 256, flags=binding.GALV_DP_BP_U8)
+    assert lib.galv_dp_workspace_bytes(ctypes.byref(bad), ctypes.byref(n)) == binding.GALV_ERR_INVALID_ARG
+    assert "255" in binding.galv_dp_last_error()
+    unknown = binding.make_desc(1, 4, 6, 256, flags=4)
+    assert lib.galv_dp_workspace_bytes(ctypes.byref(unknown), ctypes.byref(n)) == binding.GALV_ERR_INVALID_ARG
