@@ -152,8 +152,13 @@ struct Narrow {
     static __device__ __forceinline__ double dead_key(int k) {
         return __longlong_as_double((long long)(kBias | ((uint64_t)kInf32 << k)));
     }
+    // K = 2^52 + x * 2^k, built from two 32-bit operations (1 <= k <= 10): the low word is
+    // x << k; the high word is one funnel shift of {bias >> k, x} by 32 - k, which puts
+    // the bias back in place above the top k bits of x.
     static __device__ __forceinline__ double to_key(Cell x, int k) {
-        return __longlong_as_double((long long)(kBias | ((uint64_t)x << k)));
+        const uint32_t lo = x << k;
+        const uint32_t hi = __builtin_amdgcn_alignbit((uint32_t)(kBias >> 32) >> k, x, 32 - k);
+        return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
     }
     // From the reduced key: new cell = cost + c(l,s), argmin index (-1 if unreachable).
     static __device__ __forceinline__ void finish(double key, uint64_t cs, int k, uint32_t mask,
@@ -924,7 +929,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     const int group = v.ts * v.ng;
     p->groups_y = (a.S + group - 1) / group;
     a.S_pad = p->groups_y * group;
-    int k = 0;
+    int k = 1;               // at least one index bit: the key builders shift by 32 - k
     while ((1 << k) < a.S) ++k;
     a.k_bits = k;
     a.tile_e = kWave * v.te * (4 / v.ng);
