@@ -509,8 +509,10 @@ __device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int bu
     const int64_t S = a.S;
     const int k = a.k_bits;
     const int64_t pitch = a.row * kPerSlot;        // cells between rows of two strategies
+    // wave-uniform base of the previous layer's rows; the lane adds only its own column, so
+    // that the shifted addresses are a scalar base plus a loop-invariant lane offset
     const Cell *Up = reinterpret_cast<const Cell *>(a.U[(l - 1) & 1]) +
-                     (int64_t)b * a.S_pad * pitch + a.lead + e0;
+                     (int64_t)b * a.S_pad * pitch + a.lead + (e0 - lane);
     Cell *Un = reinterpret_cast<Cell *>(a.U[l & 1]) + ((int64_t)b * a.S_pad + s0) * pitch +
                a.lead + e0;
     BP *bp = static_cast<BP *>(a.bp) + (((int64_t)b * (a.L - 1) + (l - 1)) * S + s0) * a.e_pad + e0;
@@ -550,7 +552,7 @@ __device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int bu
             sps[q] = (int)(uint32_t)ent;
             const Cell *p = Up + (int64_t)(uint32_t)ent * pitch - (int64_t)(ent >> 32);
 #pragma unroll
-            for (int j = 0; j < TE; ++j) v[q][j] = p[j * kWave];
+            for (int j = 0; j < TE; ++j) v[q][j] = p[(uint32_t)lane + j * kWave];
         };
         // One entry: for each group, request the following group (of this entry or
         // of the next entry's row), reduce the current one, then await the request.
