@@ -37,7 +37,7 @@ BYTES_PER_STATE = {0: 4 + 4 + 4, 2: 8 + 8 + 4, 1: 8 + 8 + 4}   # by per-instance
 
 # HBM bytes per sweep launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by the
 # same counter's reading for a 1 GiB copy (profiles/sweep_kernel_config<N>.md); None where not measured.
-MEASURED_TRAFFIC_BYTES = {3: 753457402, 4: 3560375690}
+MEASURED_TRAFFIC_BYTES = {3: 753171149, 4: 3506451875}
 
 
 def cpu_baseline(w, seconds_hint=20.0):
@@ -73,6 +73,9 @@ def main():
                     help="store back-pointers in one byte (GALV_DP_BP_U8): 9 instead of 12 B per state")
     ap.add_argument("--streams", type=int, default=0,
                     help="internal streams the layer sweeps are spread over (0 = library's choice, 1 = none)")
+    ap.add_argument("--no-extra-legs", action="store_true",
+                    help="time only the main configuration (skip the single-stream and one-byte legs), "
+                         "so that a profile of the run holds one kind of launch")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic: 1 GiB read, "
                          "1 GiB written) so that rocprofv3 FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -153,8 +156,11 @@ def main():
     hbm_gbs = hbm_bytes / (sweep_ms * 1e-3) / 1e9
     # The same kernel with every layer as ONE launch on one stream: the per-launch figure that
     # a kernel trace shows directly (with several streams the launches overlap in time).
-    _, solve_ms_1, _, _ = timed(base_flags | binding.GALV_DP_STREAMS(1), max(2, args.steps // 2), 1)
-    launch_ms_1, achieved_1 = alu(solve_ms_1)
+    single = None
+    if not args.no_extra_legs:
+        _, solve_ms_1, _, _ = timed(base_flags | binding.GALV_DP_STREAMS(1), max(2, args.steps // 2), 1)
+        launch_ms_1, achieved_1 = alu(solve_ms_1)
+        single = {"achieved": achieved_1, "frac": achieved_1 / VALU_PEAK_TLANEOPS, "launch_ms": launch_ms_1}
 
     out = {
         "metric": "dp_cell_updates_per_sec",
@@ -184,13 +190,12 @@ def main():
                      "note": "per layer step of the whole batch; with internal streams a layer step is "
                              "several overlapping launches, so single_stream gives the one-launch-per-layer "
                              "figure that a kernel trace shows directly",
-                     "single_stream": {"achieved": achieved_1, "frac": achieved_1 / VALU_PEAK_TLANEOPS,
-                                       "launch_ms": launch_ms_1},
+                     "single_stream": single,
                      "hbm": {"achieved": hbm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                              "frac": hbm_gbs / HBM_PEAK_GBS, "bytes_per_launch": hbm_bytes,
                              "bytes_per_state": max(per_state)}},
     }
-    if not (args.bp_u8 or args.force_int64) and w.S <= 255:
+    if not (args.bp_u8 or args.force_int64 or args.no_extra_legs) and w.S <= 255:
         # NEXT-step variant, same results: one-byte back-pointers (9 instead of 12 B per state)
         ms_u8, _, _, cost_u8 = timed(binding.GALV_DP_BP_U8 | binding.GALV_DP_STREAMS(args.streams),
                                      max(2, args.steps // 2), 1)
