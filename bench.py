@@ -76,6 +76,10 @@ def main():
     ap.add_argument("--no-extra-legs", action="store_true",
                     help="time only the main configuration (skip the single-stream and one-byte legs), "
                          "so that a profile of the run holds one kind of launch")
+    ap.add_argument("--coarsen", default=None, metavar="FUSE,GRAN",
+                    help="instead of the main benchmark: time the coarse-grained search (layers fused in groups "
+                         "of FUSE, memory in units GRAN times larger) and report its cost error against the "
+                         "fine-grained optimum of the same instances")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic: 1 GiB read, "
                          "1 GiB written) so that rocprofv3 FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -106,6 +110,44 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.coarsen:
+        fuse, gran = (int(x) for x in args.coarsen.split(","))
+        fine = binding.Solver(w.B, w.L, w.S, w.E_max, w.nR)
+        fine.solve(*dev)
+        fine_cost = fine.best_cost.cpu().numpy()
+        fine.close()
+        del fine
+        torch.cuda.empty_cache()
+        Lc = (w.L + fuse - 1) // fuse
+        sol = binding.Solver(w.B, Lc, w.S, w.E_max // gran, w.nR)
+
+        def coarse_step():
+            c2, m2, r2, e2 = binding.galv_dp_coarsen(fuse, gran, *dev)
+            sol.solve(c2, m2, dev[2], r2, e2)
+            return binding.galv_dp_expand_plan(sol.backtrack(), w.L, fuse)
+
+        for _ in range(args.warmup):
+            coarse_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            coarse_step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        cost = sol.best_cost.cpu().numpy()
+        both = (fine_cost < binding.GALV_INF) & (cost < binding.GALV_INF)
+        rel = (cost[both] - fine_cost[both]) / fine_cost[both]
+        print(json.dumps({
+            "metric": "coarsened_search", "config": {"workload": f"config {args.config} '{w.name}'",
+                                                      "fuse": fuse, "granularity": gran},
+            "ms_per_step": ms, "searches_per_sec": w.B / (ms * 1e-3),
+            "layers": [w.L, Lc], "budget_columns": [w.E_max + 1, w.E_max // gran + 1],
+            "feasible_fine": int((fine_cost < binding.GALV_INF).sum()),
+            "feasible_coarse": int((cost < binding.GALV_INF).sum()),
+            "cost_error_mean": float(rel.mean()) if rel.size else None,
+            "cost_error_max": float(rel.max()) if rel.size else None}))
+        return
 
     def timed(flags, steps, warmup):
         """K steps (solve + backtrack) on a fresh handle: wall ms per step, solve ms per step."""

@@ -205,6 +205,36 @@ galv_status_t galv_alg1_reduce(int32_t n_batch, int32_t n_pp, const int32_t *pp_
                                int32_t batch_index_base, int32_t first_window, int64_t *c_p_dev,
                                galv_alg1_state_t *state_dev, void *stream);
 
+/*
+ * Coarse-grained exploration (the complexity remark that closes the "Dynamic Programming
+ * Search" paragraph of section 3.3: fuse layers, count memory in larger units), as a
+ * pre-pass that writes a smaller problem for galv_dp_solve_batched.
+ *   fuse >= 1         consecutive layers [j*fuse, min(L, (j+1)*fuse)) become fused layer j and
+ *                     run ONE strategy s:  c'(j,s) = sum of c(l,s) + sum over the group's inner
+ *                     boundaries of R_{r_idx[l]}(s,s);  the transition into the group keeps the
+ *                     selector of its first layer: r_idx'(j) = r_idx[j*fuse].  L' = ceil(L/fuse).
+ *   granularity >= 1  memory unit multiplier g:  m'(j,s) = ceil(sum of m(l,s) / g),
+ *                     budget'[b] = floor(budget[b] / g).  A (j,s) with a layer that alone exceeds
+ *                     budget[b], or whose m' exceeds budget', is marked unusable (m' = budget'+1).
+ * Rounding memory up and the budget down keeps every coarse plan feasible for the original
+ * problem at the same cost, so the coarse optimum is an upper bound of the fine one; it is
+ * exact when fuse = 1 and every m and budget is a multiple of g.
+ * Inputs as in galv_dp_solve_batched (r_idx_dev may be NULL); R is used as it is by the coarse solve.
+ *   c_out_dev [B][L'][S] int64, m_out_dev [B][L'][S] int32, r_idx_out_dev [B][L'] int32,
+ *   budget_out_dev [B] int32.
+ */
+galv_status_t galv_dp_coarsen(int32_t n_instances, int32_t n_layers, int32_t n_strategies,
+                              int32_t n_transition, int32_t fuse, int32_t granularity,
+                              const int64_t *c_dev, const int32_t *m_dev, const int64_t *R_dev,
+                              const int32_t *r_idx_dev, const int32_t *budget_dev, int64_t *c_out_dev,
+                              int32_t *m_out_dev, int32_t *r_idx_out_dev, int32_t *budget_out_dev,
+                              void *stream);
+
+/* Plan of the original layers from a plan of fused layers: plan[b][l] = coarse_plan[b][l / fuse].
+ *   coarse_plan_dev [B][ceil(L/fuse)] int32, plan_dev [B][L] out int32. */
+galv_status_t galv_dp_expand_plan(int32_t n_instances, int32_t n_layers, int32_t fuse,
+                                  const int32_t *coarse_plan_dev, int32_t *plan_dev, void *stream);
+
 /* Free the handle (host memory only; the workspace stays the caller's). NULL is allowed. */
 galv_status_t galv_dp_destroy(galv_dp_t *h);
 

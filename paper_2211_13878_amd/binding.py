@@ -35,6 +35,7 @@ GALV_INSTANCE_BAD_VALUE = -1
 EXPORTS = ("galv_dp_workspace_bytes", "galv_dp_create", "galv_dp_solve_batched",
            "galv_dp_backtrack", "galv_dp_best_per_budget", "galv_dp_backtrack_queries",
            "galv_dp_export_tables", "galv_dp_get_status", "galv_alg1_reduce",
+           "galv_dp_coarsen", "galv_dp_expand_plan",
            "galv_dp_destroy", "galv_dp_last_error")
 
 
@@ -72,6 +73,8 @@ def load_library() -> ctypes.CDLL:
         lib.galv_dp_export_tables.argtypes = [vp, i32, vp, vp, vp]
         lib.galv_dp_get_status.argtypes = [vp, vp, vp]
         lib.galv_alg1_reduce.argtypes = [i32, i32, ctypes.POINTER(i32), vp, vp, i32, i32, vp, vp, vp]
+        lib.galv_dp_coarsen.argtypes = [i32] * 6 + [vp] * 10
+        lib.galv_dp_expand_plan.argtypes = [i32, i32, i32, vp, vp, vp]
         lib.galv_dp_destroy.argtypes = [vp]
         for name in EXPORTS[:-1]:
             getattr(lib, name).restype = ctypes.c_int
@@ -172,6 +175,36 @@ def galv_alg1_reduce(pp_degree, stage_cost, batch_size, batch_index_base, first_
         n_batch, n_pp, arr, _dev_ptr(stage_cost, torch.int64), _dev_ptr(batch_size, torch.int64),
         int(batch_index_base), int(bool(first_window)), _dev_ptr(c_p, torch.int64, (n_batch, n_pp)),
         _dev_ptr(state, torch.uint8, (ALG1_STATE_BYTES,)), _stream_ptr(stream)))
+
+
+def galv_dp_coarsen(fuse, granularity, c, m, R, r_idx, budget, stream=None):
+    """Returns (c', m', r_idx', budget') device tensors of the coarse problem."""
+    B, L, S = c.shape
+    nR = R.shape[1]
+    Lc = (L + fuse - 1) // fuse
+    _dev_ptr(m, torch.int32, (B, L, S)); _dev_ptr(R, torch.int64, (B, nR, S, S)); _dev_ptr(budget, torch.int32, (B,))
+    if r_idx is not None:
+        _dev_ptr(r_idx, torch.int32, (B, L))
+    c2 = torch.empty((B, Lc, S), dtype=torch.int64, device=c.device)
+    m2 = torch.empty((B, Lc, S), dtype=torch.int32, device=c.device)
+    r2 = torch.empty((B, Lc), dtype=torch.int32, device=c.device)
+    e2 = torch.empty((B,), dtype=torch.int32, device=c.device)
+    _check(load_library().galv_dp_coarsen(
+        B, L, S, nR, int(fuse), int(granularity), _dev_ptr(c, torch.int64), _dev_ptr(m, torch.int32),
+        _dev_ptr(R, torch.int64), _dev_ptr(r_idx, torch.int32, allow_none=True), _dev_ptr(budget, torch.int32),
+        _dev_ptr(c2, torch.int64), _dev_ptr(m2, torch.int32), _dev_ptr(r2, torch.int32),
+        _dev_ptr(e2, torch.int32), _stream_ptr(stream)))
+    return c2, m2, r2, e2
+
+
+def galv_dp_expand_plan(coarse_plan, n_layers, fuse, stream=None):
+    B, Lc = coarse_plan.shape
+    if Lc != (n_layers + fuse - 1) // fuse:
+        raise GalvError(GALV_ERR_INVALID_ARG, "coarse plan length does not match n_layers and fuse")
+    plan = torch.empty((B, n_layers), dtype=torch.int32, device=coarse_plan.device)
+    _check(load_library().galv_dp_expand_plan(B, int(n_layers), int(fuse), _dev_ptr(coarse_plan, torch.int32),
+                                              _dev_ptr(plan, torch.int32), _stream_ptr(stream)))
+    return plan
 
 
 def galv_dp_destroy(h):

@@ -847,6 +847,61 @@ __global__ __launch_bounds__(kThreads) void alg1_reduce_kernel(
 }
 
 
+// ---------------------------------------------------------------------------------------------
+// Coarse-grained exploration (complexity remark at the end of section 3.3): `fuse` consecutive
+// layers become one layer that runs a single strategy, and memory is counted in units `gran`
+// times larger.  One thread per (instance, fused layer, strategy).
+__global__ __launch_bounds__(kThreads) void coarsen_kernel(
+    int B, int L, int S, int nR, int fuse, int gran, int Lc, const int64_t *__restrict__ c,
+    const int32_t *__restrict__ m, const int64_t *__restrict__ R, const int32_t *__restrict__ r_idx,
+    const int32_t *__restrict__ budget, int64_t *__restrict__ c_out, int32_t *__restrict__ m_out,
+    int32_t *__restrict__ r_idx_out, int32_t *__restrict__ budget_out) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= (int64_t)B * Lc * S) return;
+    const int s = (int)(i % S);
+    const int j = (int)((i / S) % Lc);
+    const int b = (int)(i / ((int64_t)S * Lc));
+    const int lo = j * fuse, hi = min(L, lo + fuse);
+    const int E = budget[b];
+    int64_t cost = 0, mem = 0;
+    bool unusable = false, bad_c = false, bad_m = false;   // invalid inputs stay invalid for the solver
+    for (int l = lo; l < hi; ++l) {
+        const int64_t at = ((int64_t)b * L + l) * S + s;
+        const int64_t cl = c[at];
+        bad_c |= cl < 0 || cl >= kInf;
+        cost += bad_c ? 0 : cl;
+        if (l > lo) {
+            const int r = r_idx ? r_idx[(int64_t)b * L + l] : 0;
+            const int64_t rr = (r < 0 || r >= nR) ? -1 : R[(((int64_t)b * nR + r) * S + s) * S + s];
+            bad_c |= rr < 0 || rr >= kInf;
+            cost += bad_c ? 0 : rr;
+        }
+        bad_c |= cost >= kInf;
+        const int32_t ml = m[at];
+        bad_m |= ml < 0;
+        unusable |= ml > E;
+        mem += ml;
+    }
+    const int64_t units = (mem + gran - 1) / gran;       // rounded up: a coarse plan that fits, fits
+    const int32_t Ec = E < 0 ? -1 : E / gran;
+    const int32_t over = Ec < INT32_MAX ? Ec + 1 : INT32_MAX;
+    c_out[i] = bad_c ? -1 : cost;
+    m_out[i] = bad_m ? -1 : ((unusable || units > Ec) ? over : (int32_t)units);
+    if (s == 0) {
+        r_idx_out[(int64_t)b * Lc + j] = r_idx ? r_idx[(int64_t)b * L + lo] : 0;
+        if (j == 0) budget_out[b] = Ec;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void expand_plan_kernel(int B, int L, int fuse, int Lc,
+                                                               const int32_t *__restrict__ coarse,
+                                                               int32_t *__restrict__ plan) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= (int64_t)B * L) return;
+    const int b = (int)(i / L), l = (int)(i % L);
+    plan[i] = coarse[(int64_t)b * Lc + l / fuse];
+}
+
 using SweepFn = void (*)(Layout, int);
 struct VariantEntry {
     Variant v;
@@ -1186,6 +1241,46 @@ galv_status_t galv_alg1_reduce(int32_t n_batch, int32_t n_pp, const int32_t *pp_
     alg1_reduce_kernel<<<1, kThreads, 0, static_cast<hipStream_t>(stream)>>>(
         n_batch, pp, stage_cost_dev, batch_size_dev, batch_index_base, first_window, c_p_dev,
         state_dev);
+    HIP_TRY(hipGetLastError());
+    return GALV_OK;
+}
+
+galv_status_t galv_dp_coarsen(int32_t n_instances, int32_t n_layers, int32_t n_strategies,
+                              int32_t n_transition, int32_t fuse, int32_t granularity,
+                              const int64_t *c_dev, const int32_t *m_dev, const int64_t *R_dev,
+                              const int32_t *r_idx_dev, const int32_t *budget_dev, int64_t *c_out_dev,
+                              int32_t *m_out_dev, int32_t *r_idx_out_dev, int32_t *budget_out_dev,
+                              void *stream) {
+    if (n_instances < 1 || n_layers < 1 || n_strategies < 1 || n_transition < 1)
+        return fail(GALV_ERR_INVALID_ARG, "coarsen: sizes must be >= 1");
+    if (fuse < 1 || granularity < 1)
+        return fail(GALV_ERR_INVALID_ARG, "coarsen: fuse %d and granularity %d must be >= 1", fuse,
+                    granularity);
+    if (!c_dev || !m_dev || !R_dev || !budget_dev || !c_out_dev || !m_out_dev || !r_idx_out_dev ||
+        !budget_out_dev)
+        return fail(GALV_ERR_INVALID_ARG, "a required device pointer is NULL");
+    const int Lc = (n_layers + fuse - 1) / fuse;
+    const long double cells = (long double)n_instances * Lc * n_strategies;
+    if (cells > 2.0e12L) return fail(GALV_ERR_RANGE, "coarsen: %.3Lg cells cannot be indexed", cells);
+    const int64_t n = (int64_t)n_instances * Lc * n_strategies;
+    coarsen_kernel<<<(unsigned)((n + kThreads - 1) / kThreads), kThreads, 0,
+                     static_cast<hipStream_t>(stream)>>>(
+        n_instances, n_layers, n_strategies, n_transition, fuse, granularity, Lc, c_dev, m_dev, R_dev,
+        r_idx_dev, budget_dev, c_out_dev, m_out_dev, r_idx_out_dev, budget_out_dev);
+    HIP_TRY(hipGetLastError());
+    return GALV_OK;
+}
+
+galv_status_t galv_dp_expand_plan(int32_t n_instances, int32_t n_layers, int32_t fuse,
+                                  const int32_t *coarse_plan_dev, int32_t *plan_dev, void *stream) {
+    if (n_instances < 1 || n_layers < 1 || fuse < 1)
+        return fail(GALV_ERR_INVALID_ARG, "expand_plan: sizes must be >= 1");
+    if (!coarse_plan_dev || !plan_dev) return fail(GALV_ERR_INVALID_ARG, "a required device pointer is NULL");
+    const int Lc = (n_layers + fuse - 1) / fuse;
+    const int64_t n = (int64_t)n_instances * n_layers;
+    expand_plan_kernel<<<(unsigned)((n + kThreads - 1) / kThreads), kThreads, 0,
+                         static_cast<hipStream_t>(stream)>>>(n_instances, n_layers, fuse, Lc,
+                                                             coarse_plan_dev, plan_dev);
     HIP_TRY(hipGetLastError());
     return GALV_OK;
 }
