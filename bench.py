@@ -37,7 +37,7 @@ BYTES_PER_STATE = {0: 4 + 4 + 4, 2: 8 + 8 + 4, 1: 8 + 8 + 4}   # by per-instance
 
 # HBM bytes per sweep launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by the
 # same counter's reading for a 1 GiB copy (profiles/sweep_kernel_config<N>.md); None where not measured.
-MEASURED_TRAFFIC_BYTES = {3: 753171149, 4: 3506451875}
+MEASURED_TRAFFIC_BYTES = {3: 752783314, 4: 3484726047}
 
 
 def cpu_baseline(w, seconds_hint=20.0):

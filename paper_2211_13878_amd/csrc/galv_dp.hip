@@ -601,7 +601,10 @@ __device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int bu
                 int32_t arg;
                 Store::finish(acc[s][j], cs, k, mask, cell, arg);
                 Un[(int64_t)s * pitch + j * kWave] = cell;
-                bp[(int64_t)s * a.e_pad + j * kWave] = (BP)arg;      // -1 becomes 0xFF in one byte
+                // Back-pointers are written once and read again only by the backtrack: a
+                // streaming store keeps them from pushing the cost rows, which the next
+                // layer reads back, out of the caches.  (-1 becomes 0xFF in one byte.)
+                __builtin_nontemporal_store((BP)arg, &bp[(int64_t)s * a.e_pad + j * kWave]);
             }
         }
     }
@@ -1062,14 +1065,15 @@ galv_status_t galv_dp_create(const galv_dp_desc_t *desc, void *workspace_dev,
     h->n_side = 0;
     int n = (int)((desc->flags & GALV_DP_STREAMS_MASK) >> GALV_DP_STREAMS_SHIFT);
     if (n == 0) {
-        // Automatic: enough streams to keep the chip busy across layer boundaries once a
-        // layer's sweep is long enough to pay for the extra launches.  Estimated from the
-        // shape at ~2e13 lane-operations/s.  Measured on MI355X: 5-7 and 10 streams gain
-        // 20-25 % on long sweeps, 2 gain ~15 % on mid-sized ones, multiples of 4 (the
-        // number of hardware queues) gain little, and short sweeps lose.
+        // Automatic, from the estimated duration of one layer's sweep (shape at ~2e13
+        // lane-operations/s).  Measured on MI355X with 4 hardware queues: sweeps of a few
+        // hundred microseconds gain 25-35 % from 9-10 streams (5-7 are nearly as good;
+        // multiples of 4 gain little), sweeps of tens of microseconds gain ~10 % from 2 and
+        // lose with more (host launch rate), shorter ones lose with any, and sweeps of a
+        // millisecond or more run at the arithmetic limit anyway and gain 2-5 % from 2.
         const double us = 2.0 * desc->n_instances * ((double)desc->max_budget + 1) *
                           desc->n_strategies * desc->n_strategies / 2e13 * 1e6;
-        n = us < 20.0 ? 1 : (us < 150.0 ? 2 : 6);
+        n = us < 20.0 ? 1 : (us < 150.0 ? 2 : (us < 1000.0 ? 10 : 2));
     }
     if (n > desc->n_instances) n = desc->n_instances;
     if (n > 1 && desc->n_layers > 1) {
