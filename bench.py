@@ -80,6 +80,9 @@ def main():
                     help="instead of the main benchmark: time the coarse-grained search (layers fused in groups "
                          "of FUSE, memory in units GRAN times larger) and report its cost error against the "
                          "fine-grained optimum of the same instances")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step (solve + backtrack) into a HIP graph and time replays of it: "
+                         "removes the host's per-launch cost, which dominates the small configurations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic: 1 GiB read, "
                          "1 GiB written) so that rocprofv3 FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -161,9 +164,21 @@ def main():
         # minimum, so the events bracket all of a solve's launches.
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
               for _ in range(steps)]
+        graph = None
+        if args.graph:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                sol.solve(*dev)
+                sol.backtrack()
+            graph.replay()
+            torch.cuda.synchronize()
         t0 = time.perf_counter()
         for a, b in ev:
             a.record()
+            if graph is not None:
+                graph.replay()          # the events then bracket solve + backtrack (< 1 % more)
+                b.record()
+                continue
             sol.solve(*dev)
             b.record()
             sol.backtrack()
@@ -217,6 +232,7 @@ def main():
                                f"E_max={w.E_max} budgets {int(w.budget.min())}..{int(w.budget.max())}",
                    "back_pointer_bytes": 1 if args.bp_u8 else 4,
                    "internal_streams": "auto" if args.streams == 0 else args.streams,
+                   "hip_graph_replay": bool(args.graph),
                    "cell_updates_per_batch": nominal, "exact_candidates_per_batch": exact,
                    "table_states_per_batch": states},
         "searches_per_sec": w.B / (ms_per_step * 1e-3),

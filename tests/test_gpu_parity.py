@@ -257,3 +257,34 @@ def test_runs_on_a_side_stream():
     side.synchronize()
     for b, ref in enumerate(oracle.solve_workload(w, threads=2)):
         assert int(cost[b]) == ref.best_cost and (plan[b].cpu().numpy() == ref.plan).all()
+
+
+# ------------------------------------------------------------------ size limits
+
+@pytest.mark.parametrize("S", [513, 1024])
+def test_maximum_strategy_counts(S):
+    """Up to the documented limit of 1024 strategies (32 strategy-group blocks along grid.y,
+    10 index bits in the key), both arithmetic paths, exported tables included."""
+    w = workloads.random_workload(S, 2, 3, S, 300, nR=2, m_range=(0, 120), c_range=(0, 30),
+                                  r_range=(0, 12), infeasible=0.05, zero_diagonal=False)
+    w.budget[0] = 300
+    for flags in (0, binding.GALV_DP_FORCE_INT64):
+        check_against_oracle(w, flags=flags, table_instances=[0])
+
+
+def test_very_wide_budget_axis():
+    """2^20 budget columns (8192 budget tiles), two strategies: every column against the oracle."""
+    E = 1 << 20
+    w = workloads.random_workload(3, 2, 4, 2, E, m_range=(0, E // 3), c_range=(0, 1000), r_range=(0, 50),
+                                  budgets=[E, E - 12345])
+    check_against_oracle(w, table_instances=[0, 1])
+    check_against_oracle(w, flags=binding.GALV_DP_BP_U8 | binding.GALV_DP_STREAMS(2), table_instances=[1])
+
+
+def test_many_tiny_instances():
+    """4000 instances in one launch (grid.z), ragged budgets, internal streams by the shape's default and forced."""
+    w = workloads.random_workload(12, 4000, 5, 6, 90, m_range=(0, 30), c_range=(0, 40), r_range=(0, 9),
+                                  infeasible=0.1)
+    for flags in (0, binding.GALV_DP_STREAMS(7)):
+        cost, last, plan, _ = check_against_oracle(w, flags=flags, threads=8)
+        check_properties(w, cost, last, plan)
