@@ -22,8 +22,37 @@ FLAGS = [
 ]
 
 
-def build_library(extra_flags=(), out: str = LIB) -> str:
-    """Always compiles; replaces the library atomically."""
+def device_isa(extra_flags=()) -> str:
+    """The gfx950 assembly hipcc produces for the kernels, with the library's own flags."""
+    import tempfile
+    flags = [f for f in FLAGS if f not in ("-shared", "-fPIC")]
+    with tempfile.TemporaryDirectory() as d:
+        asm = os.path.join(d, "galv_dp.s")
+        subprocess.check_call([HIPCC, *flags, *extra_flags, "-S", "--cuda-device-only", "-o", asm, SRC])
+        with open(asm) as fh:
+            return fh.read()
+
+
+def check_isa(extra_flags=()) -> int:
+    """Verify what the hand-issued scalar loads assume about the compiler's output
+    (see isa_check.py); returns the number of such loads checked, raises on a violation."""
+    from .isa_check import count_requests, scalar_prefetch_violations
+    text = device_isa(extra_flags)
+    bad = scalar_prefetch_violations(text)
+    if bad:
+        lines = "\n".join(f"  {f}: load at line {a}, line {b}: {t}" for f, a, b, t in bad[:8])
+        raise RuntimeError(f"{len(bad)} uses of scalar registers with a load still in flight; this build "
+                           f"must not run on a GPU:\n{lines}")
+    n = count_requests(text)
+    if n == 0:
+        raise RuntimeError("no s_load_dwordx16 found in the device code: the check is not looking at the sweep kernel")
+    return n
+
+
+def build_library(extra_flags=(), out: str = LIB, check: bool = True) -> str:
+    """Always compiles; checks the device code; replaces the library atomically."""
+    if check:
+        check_isa(extra_flags)
     tmp = out + f".tmp{os.getpid()}"
     cmd = [HIPCC, *FLAGS, *extra_flags, "-o", tmp, SRC]
     subprocess.check_call(cmd)

@@ -469,6 +469,12 @@ __device__ __forceinline__ void minplus(double (&acc)[TE], const double (&v)[TE]
 // A group of R keys in SGPRs: 8 * NCH doubles fetched by NCH scalar loads of 16
 // dwords.  The loads are issued by hand (the compiler would wait for each right
 // where it issues it); rgroup_await makes every later use depend on the wait.
+// Between request and await the compiler believes the destination registers are
+// already defined; were it to spill or reuse them there (it does under heavy SGPR
+// pressure, e.g. a deeper prefetch with an unsuitable tile shape), late-arriving
+// data would overwrite whatever it put there.  The build refuses such code: it
+// scans the produced assembly for any use of a destination register, any label or
+// any branch between a request and its wait (paper_2211_13878_amd/isa_check.py).
 typedef double double8 __attribute__((ext_vector_type(8)));
 template <int NCH>
 struct RGroup {
