@@ -6,16 +6,24 @@ instances that already live in HBM: galv_dp_solve_batched (preparation, layer 0,
 the L-1 layer sweeps, final minimum) followed by galv_dp_backtrack.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
+                    [--streams N] [--bp-u8] [--graph] [--no-extra-legs] [--coarsen FUSE,GRAN]
 
 Prints ONE JSON line.  `value` is DP cell-updates/s with the metric's nominal
-count sum_b L * E_b * S^2 per batch; searches/s and the exact candidate rate are
-reported beside it.  `roofline` is for the layer-sweep kernel (the only kernel
-that matters: > 99 % of the time): exact min-plus candidates per launch times
-the 2 VALU lane-operations each one needs (one 64-bit add, one 64-bit min),
-divided by the average launch duration measured with events on the launch
-stream, against the chip's VALU issue peak of 256 CUs x 64 lanes x 2.4 GHz =
-39.3 T lane-ops/s.  `cpu_baseline` times the serial CPU oracle (test
-infrastructure, never tuned) on a sample of instances of the same workload.
+count sum_b L * E_b * S^2 per batch, in the library's default configuration
+(int32 back-pointers, internal streams chosen from the shape); searches/s and
+the exact candidate rate are reported beside it.
+
+`roofline` is for the layer-sweep kernel (the only kernel that matters: > 98 %
+of the time): exact min-plus candidates of one layer times the 2 VALU
+lane-operations each one needs (one 64-bit add, one 64-bit min), divided by the
+sweep time per layer (events on the caller's stream around the solve, / (L-1)),
+against the chip's VALU issue peak of 256 CUs x 64 lanes x 2.4 GHz = 39.3 T
+lane-ops/s.  With internal streams a layer is several overlapping launches;
+`roofline.single_stream` is a second timed leg with one launch per layer, the
+figure a kernel trace of `--streams 1` shows directly.  `variant_bp_u8` is a
+third leg with one-byte back-pointers (same results, 9 instead of 12 B/state).
+`cpu_baseline` times the serial CPU oracle (test infrastructure, never tuned)
+on a sample of instances of the same workload.
 """
 from __future__ import annotations
 
