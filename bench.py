@@ -91,6 +91,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (solve + backtrack) into a HIP graph and time replays of it: "
                          "removes the host's per-launch cost, which dominates the small configurations")
+    ap.add_argument("--alg1", default=None, metavar="LAYERS,DEVICES,BUDGET",
+                    help="instead of the main benchmark: time Algorithm 1 (windowed driver over the batched "
+                         "solver) on a seeded synthetic cost model and the plain oracle loop beside it")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic: 1 GiB read, "
                          "1 GiB written) so that rocprofv3 FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -108,6 +111,37 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.alg1:
+        from paper_2211_13878_amd import alg1
+        n_layers, n_dev, budget = (int(x) for x in args.alg1.split(","))
+        model = workloads.Alg1Model(42, n_layers, n_dev, alg1.strategy_counts(n_dev))
+        sizes = range(1, 100000)
+        for _ in range(max(1, args.warmup)):
+            res = alg1.optimize(model, n_dev, budget, sizes)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            res = alg1.optimize(model, n_dev, budget, sizes)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        n_dp = (res.n_explored + 1) * (2 * n_dev - 1)          # one search per batch size, degree and stage
+        out = {"metric": "alg1_optimizations", "ms_per_step": ms,
+               "config": {"workload": f"Algorithm 1, synthetic cost model seed 42, L={n_layers}, N={n_dev}, "
+                                      f"budget {budget} units, batch sizes 1, 2, ... until Out-Of-Memory"},
+               "batch_sizes_explored": res.n_explored, "searches_needed": n_dp,
+               "searches_per_sec": n_dp / (ms * 1e-3), "best": [res.batch, res.pp, res.cost]}
+        if not args.no_cpu_baseline:
+            import oracle
+            from oracle import alg1 as oracle_alg1
+            oracle.build()
+            t0 = time.perf_counter()
+            ref = oracle_alg1.optimize(model, n_dev, budget, sizes)
+            dt = time.perf_counter() - t0
+            assert (ref["batch"], ref["pp"], ref["cost"]) == (res.batch, res.pp, res.cost)
+            out["cpu_baseline"] = {"ms": dt * 1e3, "cores": 1, "kind": "oracle"}
+        print(json.dumps(out))
+        return
+
     w = workloads.config(args.config)
     base_flags = ((binding.GALV_DP_FORCE_INT64 if args.force_int64 else 0) |
                   (binding.GALV_DP_BP_U8 if args.bp_u8 else 0))
