@@ -8,7 +8,9 @@ galv_alg1_reduce does the sums over stages, the minimum over P and the
 throughput scan with its Out-Of-Memory stop on the device.  The host reads the
 32-byte state once per window to learn whether to go on.  Batch sizes past the
 stopping one are searched speculatively and ignored, so the result is that of
-the sequential loop.
+the sequential loop.  The solves of the different pipeline degrees are independent and run
+on a stream each; every window ends with a host synchronisation, which is also what keeps
+the window's device buffers alive long enough.
 
 Host code here only marshals: it asks the cost model for tables, pads stages of
 unequal length, and decodes the result.  Stage lengths differ by at most one
@@ -53,6 +55,17 @@ def strategy_counts(n_devices: int, prune_dp_sdp: bool = True) -> dict:
             for k in range(n_devices.bit_length())}
 
 
+_streams = {}
+
+
+def _stream(device, key):
+    """Streams are kept for the life of the process: creating one costs far more than a small solve."""
+    k = (str(device), key)
+    if k not in _streams:
+        _streams[k] = torch.cuda.Stream(device=device)
+    return _streams[k]
+
+
 class _StageBatch:
     """Solver and staging buffers for one pipeline degree and one window length."""
 
@@ -74,7 +87,7 @@ class _StageBatch:
             if n < self.Ls:
                 self.m[st::pp, n:, 1:] = unusable
                 self.r_idx[st::pp, n:] = 1
-        self.plan_budget = None
+        self.stream = _stream(device, pp)                  # the degrees' solves are independent: one stream each
 
     def fill(self, model, batch_sizes):
         for ib, batch in enumerate(batch_sizes):
@@ -84,11 +97,15 @@ class _StageBatch:
                 self.c[i, :hi - lo], self.m[i, :hi - lo], self.R[i, 0] = c, m, R
 
     def solve_into(self, stage_cost, device):
-        to = lambda a: torch.from_numpy(a).to(device)
-        self.dev = (to(self.c), to(self.m), to(self.R), to(self.r_idx), self.budget)
-        s = self.solver
-        s._inputs = self.dev
-        binding.galv_dp_solve_batched(s.handle, *self.dev, stage_cost, s.best_last)
+        """Upload and solve on this degree's stream, ordered after the caller's current stream."""
+        main = torch.cuda.current_stream(device)
+        self.stream.wait_stream(main)
+        with torch.cuda.stream(self.stream):
+            to = lambda a: torch.from_numpy(a).to(device)
+            self.dev = (to(self.c), to(self.m), to(self.R), to(self.r_idx), self.budget)
+            s = self.solver
+            s._inputs = self.dev
+            binding.galv_dp_solve_batched(s.handle, *self.dev, stage_cost, s.best_last)
 
 
 def optimize(model, n_devices: int, budget: int, batch_sizes, window: int = 8,
@@ -115,6 +132,8 @@ def optimize(model, n_devices: int, budget: int, batch_sizes, window: int = 8,
             sb.fill(model, padded)
             sb.solve_into(stage_cost[off:off + window * sb.pp], device)
             off += window * sb.pp
+        for sb in stages:                                  # join: the reduction reads every degree's optima
+            torch.cuda.current_stream(device).wait_stream(sb.stream)
         c_p = torch.empty((window, len(degrees)), dtype=torch.int64, device=device)
         bs = torch.tensor(padded, dtype=torch.int64, device=device)
         if n < window:                                    # scan only the real sizes of a short last window
