@@ -296,7 +296,7 @@ def main():
                              "bytes_per_state": max(per_state)}},
     }
     if not (args.bp_u8 or args.force_int64 or args.no_extra_legs) and w.S <= 255:
-        # NEXT-step variant, same results: one-byte back-pointers (9 instead of 12 B per state)
+        # storage variant, same results: one-byte back-pointers (9 instead of 12 B per state)
         ms_u8, _, _, cost_u8 = timed(binding.GALV_DP_BP_U8 | binding.GALV_DP_STREAMS(args.streams),
                                      max(2, args.steps // 2), 1)
         assert (cost_u8 == cost).all()
