@@ -9,12 +9,14 @@ size — and, optionally, Takeaway #3 (never DP together with SDP).
 import itertools
 
 
-def count_group(group: int, prune_dp_sdp: bool) -> set:
+def count_group(group: int, prune_dp_sdp: bool, paradigms=("DP", "SDP", "TP"), ordered: bool = True) -> set:
     degrees = [d for d in (2, 4, 8, 16, 32, 64, 128, 256, 512, 1024) if d <= max(group, 2)]
     kept = set()
     for depth in range(0, 4):
-        for names in itertools.product(("DP", "SDP", "TP"), repeat=depth):
+        for names in itertools.product(paradigms, repeat=depth):
             if len(set(names)) != depth:
+                continue
+            if not ordered and list(names) != sorted(names, key=paradigms.index):
                 continue
             if prune_dp_sdp and "DP" in names and "SDP" in names:
                 continue

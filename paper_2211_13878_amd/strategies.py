@@ -34,18 +34,27 @@ def _is_pow2(x: int) -> bool:
     return x >= 1 and (x & (x - 1)) == 0
 
 
-def group_strategies(group: int, prune_dp_sdp: bool = True):
-    """Ordered (paradigm, degree) sequences for a group of `group` devices."""
+def group_strategies(group: int, prune_dp_sdp: bool = True, paradigms=PARADIGMS, ordered: bool = True):
+    """(paradigm, degree) sequences for a group of `group` devices.
+
+    `paradigms` restricts the tree to a subset (the limited search spaces the paper
+    compares against, e.g. DP+TP); `ordered=False` counts a set of levels once, in
+    the order of `paradigms`, as those systems do.
+    """
     if not _is_pow2(group):
         raise ValueError("group size must be a power of two")
+    if not set(paradigms) <= set(PARADIGMS):
+        raise ValueError("unknown paradigm")
     out = []
 
     def grow(prefix, used, remaining):
         if remaining == 1:
             out.append(tuple(prefix))
             return
-        for p in PARADIGMS:
+        for p in paradigms:
             if p in used:
+                continue
+            if not ordered and prefix and paradigms.index(p) < paradigms.index(prefix[-1][0]):
                 continue
             if prune_dp_sdp and ((p == "DP" and "SDP" in used) or (p == "SDP" and "DP" in used)):
                 continue
@@ -59,14 +68,15 @@ def group_strategies(group: int, prune_dp_sdp: bool = True):
     return out
 
 
-def enumerate_strategies(n_devices: int, prune_dp_sdp: bool = True):
-    """All candidates of one layer on `n_devices`, over PP degrees 1, 2, 4, ..., N."""
+def enumerate_strategies(n_devices: int, prune_dp_sdp: bool = True, paradigms=PARADIGMS,
+                         ordered: bool = True, pipeline: bool = True):
+    """All candidates of one layer on `n_devices`, over PP degrees 1, 2, 4, ..., N (only 1 if not `pipeline`)."""
     if not _is_pow2(n_devices):
         raise ValueError("device count must be a power of two")
     result = []
     pp = 1
-    while pp <= n_devices:
-        for levels in group_strategies(n_devices // pp, prune_dp_sdp):
+    while pp <= (n_devices if pipeline else 1):
+        for levels in group_strategies(n_devices // pp, prune_dp_sdp, tuple(paradigms), ordered):
             result.append(Strategy(pp, levels))
         pp *= 2
     return result

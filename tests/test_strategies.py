@@ -45,3 +45,14 @@ def test_rules_and_labels():
 def test_bad_sizes():
     with pytest.raises(ValueError):
         enumerate_strategies(6)
+
+
+def test_limited_search_spaces_of_the_comparison():
+    dp_tp = enumerate_strategies(8, paradigms=("DP", "TP"), ordered=False, pipeline=False)
+    assert len(dp_tp) == GOLD["dp_tp_8gpu"] == len(count_group(8, True, ("DP", "TP"), ordered=False))
+    assert {s.label for s in dp_tp} == {"8-DP", "8-TP", "2-DP x 4-TP", "4-DP x 2-TP"}
+    dp_pp = enumerate_strategies(8, paradigms=("DP",))
+    assert len(dp_pp) == GOLD["dp_pp_8gpu"]
+    assert {s.label for s in dp_pp} == {"8-DP", "2-PP / 4-DP", "4-PP / 2-DP", "8-PP / 1"}
+    # with the order of the levels counted, DP+TP alone has 6
+    assert len(enumerate_strategies(8, paradigms=("DP", "TP"), pipeline=False)) == 6
