@@ -261,6 +261,25 @@ def main():
         launch_ms_1, achieved_1 = alu(solve_ms_1)
         single = {"achieved": achieved_1, "frac": achieved_1 / VALU_PEAK_TLANEOPS, "launch_ms": launch_ms_1}
 
+    # Which roofline binds: the one that needs more time at its peak for one layer's work.
+    alu_obj = {"achieved": achieved, "peak": VALU_PEAK_TLANEOPS, "unit": "Tlane-op/s",
+               "frac": achieved / VALU_PEAK_TLANEOPS, "lane_ops_per_candidate": ops}
+    hbm_obj = {"achieved": hbm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_gbs / HBM_PEAK_GBS,
+               "bytes_per_launch": hbm_bytes, "bytes_per_state": max(per_state)}
+    t_alu = exact / n_layer_steps * ops / (VALU_PEAK_TLANEOPS * 1e12)
+    t_hbm = hbm_bytes / (HBM_PEAK_GBS * 1e9)
+    bound = "alu" if t_alu >= t_hbm else "hbm"
+    binding_obj = alu_obj if bound == "alu" else hbm_obj
+    roofline = {"bound": bound, "kernel": "sweep_kernel", "achieved": binding_obj["achieved"],
+                "peak": binding_obj["peak"], "unit": binding_obj["unit"], "frac": binding_obj["frac"],
+                "traffic": None if (args.force_int64 or args.bp_u8) else MEASURED_TRAFFIC_BYTES.get(args.config),
+                "launch_ms": sweep_ms,
+                "time_at_peak_us": {"alu": t_alu * 1e6, "hbm": t_hbm * 1e6},
+                "note": "per layer step of the whole batch; with internal streams a layer step is "
+                        "several overlapping launches, so single_stream gives the one-launch-per-layer "
+                        "figure that a kernel trace shows directly (ALU fraction)",
+                "single_stream": single, "alu": alu_obj, "hbm": hbm_obj}
+
     out = {
         "metric": "dp_cell_updates_per_sec",
         "value": nominal / (ms_per_step * 1e-3),
@@ -282,18 +301,7 @@ def main():
         "solve_ms_median": solve_ms[len(solve_ms) // 2],
         "instances_fast_path": int((status == binding.GALV_INSTANCE_OK_FAST).sum()),
         "instances_feasible": int((cost < binding.GALV_INF).sum()),
-        "roofline": {"bound": "alu", "kernel": "sweep_kernel", "achieved": achieved,
-                     "peak": VALU_PEAK_TLANEOPS, "unit": "Tlane-op/s",
-                     "frac": achieved / VALU_PEAK_TLANEOPS,
-                     "traffic": None if (args.force_int64 or args.bp_u8) else MEASURED_TRAFFIC_BYTES.get(args.config),
-                     "launch_ms": sweep_ms, "lane_ops_per_candidate": ops,
-                     "note": "per layer step of the whole batch; with internal streams a layer step is "
-                             "several overlapping launches, so single_stream gives the one-launch-per-layer "
-                             "figure that a kernel trace shows directly",
-                     "single_stream": single,
-                     "hbm": {"achieved": hbm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                             "frac": hbm_gbs / HBM_PEAK_GBS, "bytes_per_launch": hbm_bytes,
-                             "bytes_per_state": max(per_state)}},
+        "roofline": roofline,
     }
     if not (args.bp_u8 or args.force_int64 or args.no_extra_legs) and w.S <= 255:
         # storage variant, same results: one-byte back-pointers (9 instead of 12 B per state)
