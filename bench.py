@@ -14,9 +14,10 @@ count sum_b L * E_b * S^2 per batch, in the library's default configuration
 the exact candidate rate are reported beside it.
 
 `roofline` is for the layer-sweep kernel (the only kernel that matters: > 98 %
-of the time): exact min-plus candidates of one layer times the 2 VALU
-lane-operations each one needs (one 64-bit add, one 64-bit min), divided by the
-sweep time per layer (events on the caller's stream around the solve, / (L-1)),
+of the time): exact min-plus candidates of one layer times the VALU
+lane-operations each one needs on its instance's arithmetic path (1.5 with
+32-bit keys: two adds and one three-way minimum per two candidates; 2 with
+64-bit keys: one add, one minimum), divided by the sweep time per layer (events on the caller's stream around the solve, / (L-1)),
 against the chip's VALU issue peak of 256 CUs x 64 lanes x 2.4 GHz = 39.3 T
 lane-ops/s.  With internal streams a layer is several overlapping launches;
 `roofline.single_stream` is a second timed leg with one launch per layer, the
@@ -38,14 +39,17 @@ sys.path.insert(0, ROOT)
 
 VALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12      # 39.3
 HBM_PEAK_GBS = 8000.0
-OPS_PER_CANDIDATE = 2                              # v_add_f64 + v_min_f64
+# VALU lane-operations one min-plus candidate needs, by the arithmetic path of its instance
+# (status code): 32-bit keys fold two candidates into two adds and one three-way minimum;
+# 64-bit keys take one add and one minimum each; the general integer path about six.
+OPS_PER_CANDIDATE = {3: 1.5, 0: 2.0, 2: 2.0, 1: 6.0}
 # table bytes per state: cost cell read + cost cell written + int32 back-pointer written
-BYTES_PER_STATE = {0: 4 + 4 + 4, 2: 8 + 8 + 4, 1: 8 + 8 + 4}   # by per-instance status code
+BYTES_PER_STATE = {3: 4 + 4 + 4, 0: 4 + 4 + 4, 2: 8 + 8 + 4, 1: 8 + 8 + 4}   # by per-instance status code
 
 
 # HBM bytes per sweep launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by the
 # same counter's reading for a 1 GiB copy (profiles/sweep_kernel_config<N>.md); None where not measured.
-MEASURED_TRAFFIC_BYTES = {3: 752783314, 4: 3484726047}
+MEASURED_TRAFFIC_BYTES = {3: 949922265, 4: 2706109147}
 
 
 def cpu_baseline(w, seconds_hint=20.0):
@@ -77,6 +81,7 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload index 0..4 (default 3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--force-int64", action="store_true", help="time the general integer kernels")
+    ap.add_argument("--no-u32", action="store_true", help="keep 64-bit keys (GALV_DP_NO_U32)")
     ap.add_argument("--bp-u8", action="store_true",
                     help="store back-pointers in one byte (GALV_DP_BP_U8): 9 instead of 12 B per state")
     ap.add_argument("--streams", type=int, default=0,
@@ -144,6 +149,7 @@ def main():
 
     w = workloads.config(args.config)
     base_flags = ((binding.GALV_DP_FORCE_INT64 if args.force_int64 else 0) |
+                  (binding.GALV_DP_NO_U32 if args.no_u32 else 0) |
                   (binding.GALV_DP_BP_U8 if args.bp_u8 else 0))
     dev = binding.upload(w)
     torch.cuda.synchronize()
@@ -238,17 +244,20 @@ def main():
     exact = w.exact_candidates()
     states = w.n_states()
     n_layer_steps = max(1, w.L - 1)
-    ops = OPS_PER_CANDIDATE if not args.force_int64 else 6
 
     def alu(solve_ms):
         """Sweep lane-ops per layer step over its duration (prep / init / final are < 1 % and
         counted into the duration, so this is a lower bound)."""
         layer_ms = sum(solve_ms) / len(solve_ms) / n_layer_steps
-        achieved = exact / n_layer_steps * ops / (layer_ms * 1e-3) / 1e12
+        achieved = lane_ops_per_layer / (layer_ms * 1e-3) / 1e12
         return layer_ms, achieved
 
     ms_per_step, solve_ms, status, cost = timed(base_flags | binding.GALV_DP_STREAMS(args.streams),
                                                 args.steps, args.warmup)
+    # lane-ops of one layer: per instance (E_b + 1) * S^2 candidates times its path's cost
+    lane_ops_per_layer = sum(OPS_PER_CANDIDATE.get(int(st), 0.0) * (int(e) + 1) * w.S * w.S
+                             for st, e in zip(status, w.budget))
+    ops = lane_ops_per_layer / max(1, exact / n_layer_steps)
     sweep_ms, achieved = alu(solve_ms)
     per_state = [BYTES_PER_STATE.get(int(st), 0) - (3 if args.bp_u8 else 0) for st in status]
     hbm_bytes = sum(p * (int(e) + 1) * w.S for p, e in zip(per_state, w.budget))   # per layer
@@ -266,7 +275,7 @@ def main():
                "frac": achieved / VALU_PEAK_TLANEOPS, "lane_ops_per_candidate": ops}
     hbm_obj = {"achieved": hbm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_gbs / HBM_PEAK_GBS,
                "bytes_per_launch": hbm_bytes, "bytes_per_state": max(per_state)}
-    t_alu = exact / n_layer_steps * ops / (VALU_PEAK_TLANEOPS * 1e12)
+    t_alu = lane_ops_per_layer / (VALU_PEAK_TLANEOPS * 1e12)
     t_hbm = hbm_bytes / (HBM_PEAK_GBS * 1e9)
     bound = "alu" if t_alu >= t_hbm else "hbm"
     binding_obj = alu_obj if bound == "alu" else hbm_obj
@@ -299,7 +308,10 @@ def main():
         "searches_per_sec": w.B / (ms_per_step * 1e-3),
         "exact_candidates_per_sec": exact / (ms_per_step * 1e-3),
         "solve_ms_median": solve_ms[len(solve_ms) // 2],
-        "instances_fast_path": int((status == binding.GALV_INSTANCE_OK_FAST).sum()),
+        "instances_by_path": {"u32_keys": int((status == binding.GALV_INSTANCE_OK_FAST_U32).sum()),
+                              "f64_keys_32bit_cells": int((status == binding.GALV_INSTANCE_OK_FAST).sum()),
+                              "f64_keys_64bit_cells": int((status == binding.GALV_INSTANCE_OK_FAST_WIDE).sum()),
+                              "int64": int((status == binding.GALV_INSTANCE_OK_INT64).sum())},
         "instances_feasible": int((cost < binding.GALV_INF).sum()),
         "roofline": roofline,
     }

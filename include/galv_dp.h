@@ -81,6 +81,8 @@ typedef struct {
                                   Shrinks the largest table of the workspace and the dominant
                                   HBM write of the sweep by 4x */
 
+#define GALV_DP_NO_U32 4u      /* do not use the 32-bit integer-key kernels (see
+                                  GALV_INSTANCE_OK_FAST_U32); the 64-bit-key ones take over   */
 #define GALV_DP_STREAMS_SHIFT 8 /* bits 8..12: how many internal streams the layer sweeps are   */
 #define GALV_DP_STREAMS_MASK 0x1f00u /* spread over; 0 = chosen from the shape, 1 = none, at most 16 */
 #define GALV_DP_STREAMS(n) ((uint32_t)(n) << GALV_DP_STREAMS_SHIFT)
@@ -91,6 +93,9 @@ typedef struct {
 #define GALV_INSTANCE_OK_INT64 1     /* general 64-bit integer kernels                      */
 #define GALV_INSTANCE_OK_FAST_WIDE 2 /* packed-key kernels, costs stored in 64 bits (cost
                                         times the next power of two >= S stays below 2^52)  */
+#define GALV_INSTANCE_OK_FAST_U32 3   /* as OK_FAST and, besides, (2 * largest R + 2) * 2^k <= 2^32
+                                        (k = index bits): keys of relative costs in 32-bit
+                                        integers, three instructions per two candidates      */
 #define GALV_INSTANCE_BAD_VALUE (-1) /* a value violates the preconditions above            */
 
 /*

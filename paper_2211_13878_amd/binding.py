@@ -23,13 +23,14 @@ GALV_OK = 0
 GALV_ERR_INVALID_ARG, GALV_ERR_WORKSPACE, GALV_ERR_RANGE, GALV_ERR_HIP, GALV_ERR_STATE = 1, 2, 3, 4, 5
 GALV_DP_FORCE_INT64 = 1
 GALV_DP_BP_U8 = 2
+GALV_DP_NO_U32 = 4
 
 
 def GALV_DP_STREAMS(n: int) -> int:
     """Flag bits asking for n internal streams (0 = automatic, 1 = none)."""
     return int(n) << 8
 
-GALV_INSTANCE_OK_FAST, GALV_INSTANCE_OK_INT64, GALV_INSTANCE_OK_FAST_WIDE = 0, 1, 2
+GALV_INSTANCE_OK_FAST, GALV_INSTANCE_OK_INT64, GALV_INSTANCE_OK_FAST_WIDE, GALV_INSTANCE_OK_FAST_U32 = 0, 1, 2, 3
 GALV_INSTANCE_BAD_VALUE = -1
 
 EXPORTS = ("galv_dp_workspace_bytes", "galv_dp_create", "galv_dp_solve_batched",

@@ -45,6 +45,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <type_traits>
 
 #include "../../include/galv_dp.h"
 
@@ -56,6 +57,9 @@ constexpr int kEAlign = 1024;          // budget columns are padded to this
 constexpr int kMaxS = 1024;
 constexpr int kMaxSide = 16;          // internal streams per handle
 constexpr int kMaxPp = 16;            // pipeline degrees per reduce call
+#ifndef GALV_P1_BATCH
+#define GALV_P1_BATCH 8
+#endif
 #ifndef GALV_DEPTH
 #define GALV_DEPTH 2
 #endif
@@ -86,7 +90,7 @@ inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // Geometry of one sweep-kernel variant: TS strategies x TE budget columns of
 // running minima per lane, NG strategy groups per workgroup.
 struct Variant {
-    int ts, te, ng;
+    int ts, te, ng, w, ux; // w: wavefronts per workgroup (w / ng budget sub-tiles); ux: see sweep_kernel
 };
 
 // Everything the kernels need to find their data.  Passed by value.
@@ -107,6 +111,7 @@ struct Layout {
     uint64_t *ck;         // per-mode c(l,s)     [B][L][S_pad]
     uint64_t *vlist;      // usable strategies of each layer, ascending: shift << 32 | s'  [B][L][S]
     int32_t *nvalid;      // how many of them    [B][L]
+    uint32_t *dclamp;     // 32-bit-key path: largest R + 1, the clamp of relative costs  [B]
     int32_t *status;      // per instance        [B]
     int32_t *last;        // best last strategy  [B]
     const int64_t *c;
@@ -126,6 +131,11 @@ using ConstPtr = const T __attribute__((address_space(4))) *;
 template <class T>
 __device__ __forceinline__ ConstPtr<T> as_const(const T *p) {
     return (ConstPtr<T>)(uintptr_t)p;
+}
+
+// Storage of the cost rows: 32-bit cells for both packed-key paths of small costs.
+__device__ __forceinline__ bool narrow_cells(int st) {
+    return st == GALV_INSTANCE_OK_FAST || st == GALV_INSTANCE_OK_FAST_U32;
 }
 
 // Back-pointer of un-shifted cell idx, whichever width the handle stores.
@@ -296,7 +306,12 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
         } else if (flags & GALV_DP_FORCE_INT64) {
             st = GALV_INSTANCE_OK_INT64;
         } else if (bound + rmax_all < kInf32) {
-            st = GALV_INSTANCE_OK_FAST;         // costs, and infinity + R, fit 32 bits
+            // costs, and infinity + R, fit 32 bits.  If, besides, twice the largest R still
+            // leaves room for the index in a 32-bit key, the integer path applies.
+            const bool u32 = !(flags & GALV_DP_NO_U32) &&
+                             ((2 * rmax_all + 2) << a.k_bits) <= (1ull << 32);
+            st = u32 ? GALV_INSTANCE_OK_FAST_U32 : GALV_INSTANCE_OK_FAST;
+            a.dclamp[b] = (uint32_t)(rmax_all + 1);
         } else if (bound + 1 <= (1ull << (52 - a.k_bits))) {
             st = GALV_INSTANCE_OK_FAST_WIDE;    // keys fit the 52-bit mantissa
         } else {
@@ -307,17 +322,30 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
     }
     __syncthreads();
     const int st = status_s;
-    if (st != GALV_INSTANCE_OK_FAST && st != GALV_INSTANCE_OK_FAST_WIDE) return;
+    if (!narrow_cells(st) && st != GALV_INSTANCE_OK_FAST_WIDE) return;
 
     // R key = R * 2^k + s' (s' = row = former strategy); padded columns are +inf so
     // that they never win and never read past the caller's matrix.
     const double scale = (double)(1ull << a.k_bits);
     double *Rk = a.Rk + (int64_t)b * nR * S * a.S_pad;
-    for (int64_t i = tid; i < nR * S * a.S_pad; i += kThreads) {
-        const int64_t s = i % a.S_pad;
-        const int64_t sp = (i / a.S_pad) % S;
-        const int64_t k = i / (a.S_pad * S);
-        Rk[i] = (s < S) ? (double)R[(k * S + sp) * S + s] * scale + (double)sp : INFINITY;
+    if (st == GALV_INSTANCE_OK_FAST_U32) {
+        // 32-bit keys in the first half of each matrix's slot: rows of S_pad words, one matrix
+        // every S * S_pad doubles; padded columns hold the largest word.
+        for (int64_t i = tid; i < nR * S * a.S_pad; i += kThreads) {
+            const int64_t s = i % a.S_pad;
+            const int64_t sp = (i / a.S_pad) % S;
+            const int64_t k = i / (a.S_pad * S);
+            uint32_t *row = reinterpret_cast<uint32_t *>(Rk + k * S * a.S_pad) + sp * a.S_pad;
+            row[s] = (s < S) ? (((uint32_t)R[(k * S + sp) * S + s]) << a.k_bits) | (uint32_t)sp
+                             : 0xffffffffu;
+        }
+    } else {
+        for (int64_t i = tid; i < nR * S * a.S_pad; i += kThreads) {
+            const int64_t s = i % a.S_pad;
+            const int64_t sp = (i / a.S_pad) % S;
+            const int64_t k = i / (a.S_pad * S);
+            Rk[i] = (s < S) ? (double)R[(k * S + sp) * S + s] * scale + (double)sp : INFINITY;
+        }
     }
     // c(l,s) in the form the epilogue adds: the integer itself (narrow) or the
     // double c * 2^k (wide).
@@ -325,7 +353,7 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
     for (int64_t i = tid; i < L * a.S_pad; i += kThreads) {
         const int64_t s = i % a.S_pad, l = i / a.S_pad;
         const int64_t v = (s < S) ? c[l * S + s] : 0;
-        ck[i] = (st == GALV_INSTANCE_OK_FAST)
+        ck[i] = narrow_cells(st)
                     ? (uint64_t)v
                     : (uint64_t)__double_as_longlong((double)v * scale);
     }
@@ -359,7 +387,7 @@ __global__ __launch_bounds__(kThreads) void init_kernel(Layout a) {
         return;
     }
     const uint64_t cs = a.ck[((int64_t)b * a.L) * a.S_pad + s];
-    if (st == GALV_INSTANCE_OK_FAST) {
+    if (narrow_cells(st)) {
         uint32_t *u0 = reinterpret_cast<uint32_t *>(a.U[0] + base);
         uint32_t *u1 = reinterpret_cast<uint32_t *>(a.U[1] + base);
         if (x < a.lead) {
@@ -397,7 +425,7 @@ __device__ __forceinline__ void sweep_int64(const Layout &a, int l, int b, int b
     const int r = a.r_idx ? a.r_idx[(int64_t)b * a.L + l] : 0;
     const int64_t *R = a.R + ((int64_t)b * a.nR + r) * S * S;
 
-    for (int64_t e = tile_start + threadIdx.x; e < tile_start + a.tile_e; e += kThreads) {
+    for (int64_t e = tile_start + threadIdx.x; e < tile_start + a.tile_e; e += blockDim.x) {
         if (e > budget) continue;
         for (int64_t s0 = 0; s0 < S; s0 += CH) {
             int64_t best[CH];
@@ -616,18 +644,268 @@ __device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int bu
     }
 }
 
-template <int TS, int TE, int NG, int WPE, class BP>
-__global__ __launch_bounds__(kThreads, WPE) void sweep_kernel(Layout a, int l) {
+// ------------------------------------------------------- 32-bit integer keys
+//
+// When costs fit 32 bits and twice the largest transition cost R_max still leaves
+// room for the index, the inner minimum runs on 32-bit integers, two candidates per
+// three instructions (two adds and one three-way minimum) instead of two per four.
+// Costs are taken RELATIVE to the column's smallest former cost Cmin(e') =
+// min_{s'} C[l-1][e'][s'] and clamped at D = R_max + 1:
+//     key(s') = (min(C[l-1][e'][s'] - Cmin, D) + R(s', s)) * 2^k + s'   <  2^32.
+// Clamping changes no result: the former strategy that attains Cmin gives a
+// candidate of at most Cmin + R_max, while a clamped one costs at least
+// Cmin + R_max + 1, so it neither wins nor ties.  Cmin comes from a first pass over
+// the same shifted cells (they are then read again from the caches).  The new cell
+// is Cmin + (key >> k) + c(l, s); a column without any reachable former cell
+// (Cmin = infinity) stays infinity.
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+typedef uint32_t uint8v __attribute__((ext_vector_type(8)));
+typedef uint32_t uint16v __attribute__((ext_vector_type(16)));
+
+// The R keys of one former strategy for TS strategy columns, in as few scalar registers as
+// the loads allow (8, 8 + 4 or 16): four such rows are live at a time.
+template <int TS, class = void>
+struct R32Row;
+template <int TS>
+struct R32Row<TS, std::enable_if_t<(TS <= 8)>> {
+    uint8v lo;
+    uint32_t hi = 0;       // (unused; keeps the three shapes alike)
+    __device__ __forceinline__ uint32_t at(int s) const { return lo[s]; }
+    __device__ __forceinline__ void request(ConstPtr<uint32_t> p) {
+        asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=&s"(lo) : "s"(p));
+    }
+    __device__ __forceinline__ void tie() { asm volatile("" : "+s"(lo)); }
+};
+template <int TS>
+struct R32Row<TS, std::enable_if_t<(TS > 8 && TS <= 12)>> {
+    uint8v lo;
+    uint4v hi;
+    __device__ __forceinline__ uint32_t at(int s) const { return s < 8 ? lo[s] : hi[s - 8]; }
+    __device__ __forceinline__ void request(ConstPtr<uint32_t> p) {
+        asm volatile("s_load_dwordx8 %0, %2, 0x0\n\ts_load_dwordx4 %1, %2, 0x20"
+                     : "=&s"(lo), "=&s"(hi)
+                     : "s"(p));
+    }
+    __device__ __forceinline__ void tie() { asm volatile("" : "+s"(lo), "+s"(hi)); }
+};
+template <int TS>
+struct R32Row<TS, std::enable_if_t<(TS > 12)>> {
+    uint16v lo;
+    uint32_t hi = 0;       // (unused; keeps the three shapes alike)
+    __device__ __forceinline__ uint32_t at(int s) const { return lo[s]; }
+    __device__ __forceinline__ void request(ConstPtr<uint32_t> p) {
+        asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=&s"(lo) : "s"(p));
+    }
+    __device__ __forceinline__ void tie() { asm volatile("" : "+s"(lo)); }
+};
+// Wait for every outstanding scalar load; the rows passed in become usable only after it.
+template <class Row>
+__device__ __forceinline__ void r32_await(Row &g0, Row &g1) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    g0.tie();
+    g1.tie();
+}
+
+// acc = min(acc, va + ra, vb + rb) per budget column.  `keep...` are the registers of the
+// rows still being loaded: naming them as (unused) inputs of every statement between their
+// request and their wait keeps their next use close, so the register allocator has no
+// reason to spill or move them while the loads are in flight.
+template <int TE, class Row>
+__device__ __forceinline__ void minplus_u32x2(uint32_t (&acc)[TE], const uint32_t (&va)[TE],
+                                              const uint32_t (&vb)[TE], uint32_t ra, uint32_t rb,
+                                              const Row &ka, const Row &kb) {
+    static_assert(TE == 1 || TE == 2 || TE == 4, "budget columns per lane");
+    if constexpr (TE == 1) {
+        uint32_t t0, t1;
+        asm("v_add_u32 %1, %5, %3\n\tv_add_u32 %2, %6, %4\n\tv_min3_u32 %0, %0, %1, %2"
+            : "+v"(acc[0]), "=&v"(t0), "=&v"(t1)
+            : "v"(va[0]), "v"(vb[0]), "s"(ra), "s"(rb), "s"(ka.lo), "s"(ka.hi), "s"(kb.lo), "s"(kb.hi));
+    } else if constexpr (TE == 2) {
+        uint32_t t0, t1, t2, t3;
+        asm("v_add_u32 %2, %10, %6\n\tv_add_u32 %3, %11, %8\n\t"
+            "v_add_u32 %4, %10, %7\n\tv_add_u32 %5, %11, %9\n\t"
+            "v_min3_u32 %0, %0, %2, %3\n\tv_min3_u32 %1, %1, %4, %5"
+            : "+v"(acc[0]), "+v"(acc[1]), "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3)
+            : "v"(va[0]), "v"(va[1]), "v"(vb[0]), "v"(vb[1]), "s"(ra), "s"(rb), "s"(ka.lo), "s"(ka.hi),
+              "s"(kb.lo), "s"(kb.hi));
+    } else {
+        uint32_t t0, t1, t2, t3, t4, t5, t6, t7;
+        asm("v_add_u32 %4, %20, %12\n\tv_add_u32 %5, %21, %16\n\t"
+            "v_add_u32 %6, %20, %13\n\tv_add_u32 %7, %21, %17\n\t"
+            "v_add_u32 %8, %20, %14\n\tv_add_u32 %9, %21, %18\n\t"
+            "v_add_u32 %10, %20, %15\n\tv_add_u32 %11, %21, %19\n\t"
+            "v_min3_u32 %0, %0, %4, %5\n\tv_min3_u32 %1, %1, %6, %7\n\t"
+            "v_min3_u32 %2, %2, %8, %9\n\tv_min3_u32 %3, %3, %10, %11"
+            : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "=&v"(t0), "=&v"(t1),
+              "=&v"(t2), "=&v"(t3), "=&v"(t4), "=&v"(t5), "=&v"(t6), "=&v"(t7)
+            : "v"(va[0]), "v"(va[1]), "v"(va[2]), "v"(va[3]), "v"(vb[0]), "v"(vb[1]), "v"(vb[2]),
+              "v"(vb[3]), "s"(ra), "s"(rb), "s"(ka.lo), "s"(ka.hi), "s"(kb.lo), "s"(kb.hi));
+    }
+}
+
+template <int TS, int TE, int NG, class BP>
+__device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int budget,
+                                          int64_t tile_start) {
+    static_assert(TS <= 16, "one scalar load fetches the R keys of a row");
+    const int wave = uniform(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int g = wave % NG;
+    const int esub = wave / NG;
+    const int64_t e0 = tile_start + (int64_t)esub * (kWave * TE) + lane;
+    const int64_t s0 = ((int64_t)blockIdx.y * NG + g) * TS;
+    if (s0 >= a.S) return;
+    if (tile_start + (int64_t)esub * (kWave * TE) > budget) return;
+
+    const int64_t S = a.S;
+    const int k = a.k_bits;
+    const int64_t pitch = a.row * 2;               // 32-bit cells between the rows of two strategies
+    const uint32_t *Up = reinterpret_cast<const uint32_t *>(a.U[(l - 1) & 1]) +
+                         (int64_t)b * a.S_pad * pitch + a.lead + (e0 - lane);
+    uint32_t *Un = reinterpret_cast<uint32_t *>(a.U[l & 1]) + ((int64_t)b * a.S_pad + s0) * pitch +
+                   a.lead + e0;
+    BP *bp = static_cast<BP *>(a.bp) + (((int64_t)b * (a.L - 1) + (l - 1)) * S + s0) * a.e_pad + e0;
+    const int r = a.r_idx ? a.r_idx[(int64_t)b * a.L + l] : 0;
+    const ConstPtr<uint32_t> Rk =
+        as_const(reinterpret_cast<const uint32_t *>(a.Rk + ((int64_t)b * a.nR + r) * S * a.S_pad) + s0);
+    const ConstPtr<uint64_t> ck = as_const(a.ck + ((int64_t)b * a.L + l) * a.S_pad + s0);
+    const ConstPtr<uint64_t> vl = as_const(a.vlist + ((int64_t)b * a.L + (l - 1)) * S);
+    const int n = as_const(a.nvalid)[(int64_t)b * a.L + (l - 1)];
+    const uint32_t dmax = as_const(a.dclamp)[b];
+
+    uint32_t acc[TS][TE];
+#pragma unroll
+    for (int s = 0; s < TS; ++s)
+#pragma unroll
+        for (int j = 0; j < TE; ++j) acc[s][j] = 0xffffffffu;
+    uint32_t cmin[TE];
+#pragma unroll
+    for (int j = 0; j < TE; ++j) cmin[j] = 0xffffffffu;
+
+    auto cells = [&](int i) {            // shifted row of list entry i (clamped to the list)
+        const uint64_t ent = vl[i < n ? i : n - 1];
+        return Up + (int64_t)(uint32_t)ent * pitch - (int64_t)(ent >> 32);
+    };
+
+    if (n > 0) {
+        // Pass 1: the column minima of the former layer.  Pure loads: batches of kBatch list
+        // entries, the next batch requested before the current one is reduced.
+        constexpr int kBatch = GALV_P1_BATCH;
+        uint32_t t[2][kBatch][TE];
+        auto fetch = [&](int h, int i0) {
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const uint32_t *p = cells(i0 + u);
+#pragma unroll
+                for (int j = 0; j < TE; ++j) t[h][u][j] = p[(uint32_t)lane + j * kWave];
+            }
+        };
+        auto fold = [&](int h) {
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u)
+#pragma unroll
+                for (int j = 0; j < TE; ++j) cmin[j] = min(cmin[j], t[h][u][j]);
+        };
+        fetch(0, 0);
+        int i = 0;
+        for (; i + 2 * kBatch < n; i += 2 * kBatch) {
+            fetch(1, i + kBatch);
+            fold(0);
+            fetch(0, i + 2 * kBatch);
+            fold(1);
+        }
+        if (i + kBatch < n) {
+            fetch(1, i + kBatch);
+            fold(0);
+            fold(1);
+        } else {
+            fold(0);
+        }
+
+        // Pass 2: pairs of list entries.  The cells of the next pair and the R rows of the
+        // next pair are requested before the current pair is reduced.
+        const int npair = (n + 1) / 2;             // an odd tail repeats its entry: min(x, x) = x
+        uint32_t va[2][TE], vb[2][TE];
+        int spa[2], spb[2];
+        R32Row<TS> ra[2], rb[2];
+        auto request = [&](int q, int pr) {
+            const int ia = 2 * pr < n ? 2 * pr : n - 1;
+            const int ib = 2 * pr + 1 < n ? 2 * pr + 1 : n - 1;
+            const uint64_t ea = vl[ia], eb = vl[ib];
+            spa[q] = (int)(uint32_t)ea;
+            spb[q] = (int)(uint32_t)eb;
+            const uint32_t *pa = Up + (int64_t)(uint32_t)ea * pitch - (int64_t)(ea >> 32);
+            const uint32_t *pb = Up + (int64_t)(uint32_t)eb * pitch - (int64_t)(eb >> 32);
+#pragma unroll
+            for (int j = 0; j < TE; ++j) {
+                va[q][j] = pa[(uint32_t)lane + j * kWave];
+                vb[q][j] = pb[(uint32_t)lane + j * kWave];
+            }
+        };
+        auto reduce_pair = [&](int q) {
+            // keys of the next pair's rows, in flight under this pair's arithmetic
+            ra[q ^ 1].request(Rk + (int64_t)spa[q ^ 1] * a.S_pad);
+            rb[q ^ 1].request(Rk + (int64_t)spb[q ^ 1] * a.S_pad);
+            uint32_t da[TE], db[TE];
+#pragma unroll
+            for (int j = 0; j < TE; ++j) {
+                da[j] = min(va[q][j] - cmin[j], dmax) << k;
+                db[j] = min(vb[q][j] - cmin[j], dmax) << k;
+            }
+#pragma unroll
+            for (int s = 0; s < TS; ++s)
+                minplus_u32x2<TE>(acc[s], da, db, ra[q].at(s), rb[q].at(s), ra[q ^ 1], rb[q ^ 1]);
+            r32_await(ra[q ^ 1], rb[q ^ 1]);
+        };
+        request(0, 0);
+        request(1, 1);
+        ra[0].request(Rk + (int64_t)spa[0] * a.S_pad);
+        rb[0].request(Rk + (int64_t)spb[0] * a.S_pad);
+        r32_await(ra[0], rb[0]);
+        int pr = 0;
+        for (; pr + 2 <= npair; pr += 2) {
+            reduce_pair(0);
+            request(0, pr + 2);
+            reduce_pair(1);
+            request(1, pr + 3);
+        }
+        if (pr < npair) reduce_pair(0);
+    }
+
+    const uint32_t mask = (1u << k) - 1u;
+#pragma unroll
+    for (int s = 0; s < TS; ++s) {
+        if (s0 + s < S) {
+            const uint32_t cs = (uint32_t)ck[s];
+#pragma unroll
+            for (int j = 0; j < TE; ++j) {
+                const bool alive = cmin[j] < kInf32;
+                const uint32_t key = acc[s][j];
+                Un[(int64_t)s * pitch + j * kWave] = alive ? cmin[j] + (key >> k) + cs : kInf32;
+                __builtin_nontemporal_store((BP)(alive ? (int32_t)(key & mask) : -1),
+                                            &bp[(int64_t)s * a.e_pad + j * kWave]);
+            }
+        }
+    }
+}
+
+// UX: the 32-bit-key body keeps half-size accumulators, so it may take UX (1 or 2) times
+// the budget columns per lane; the 64-bit-key bodies then cover the same tile in UX steps.
+template <int TS, int TE, int NG, int WPE, class BP, int W, int UX>
+__global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) {
     const int b = a.b_off + blockIdx.z * a.b_step;
     const int st = a.status[b];
     if (st < 0) return;
     const int budget = a.budget[b];
     const int64_t tile_start = (int64_t)blockIdx.x * a.tile_e;
     if (tile_start > budget) return;
-    if (st == GALV_INSTANCE_OK_FAST) {
-        sweep_fast<TS, TE, NG, Narrow, BP>(a, l, b, budget, tile_start);
+    if (st == GALV_INSTANCE_OK_FAST_U32) {
+        sweep_u32<TS, TE * UX, NG, BP>(a, l, b, budget, tile_start);
+    } else if (st == GALV_INSTANCE_OK_FAST) {
+        for (int h = 0; h < UX; ++h)
+            sweep_fast<TS, TE, NG, Narrow, BP>(a, l, b, budget, tile_start + h * (a.tile_e / UX));
     } else if (st == GALV_INSTANCE_OK_FAST_WIDE) {
-        sweep_fast<TS, TE, NG, Wide, BP>(a, l, b, budget, tile_start);
+        for (int h = 0; h < UX; ++h)
+            sweep_fast<TS, TE, NG, Wide, BP>(a, l, b, budget, tile_start + h * (a.tile_e / UX));
     } else {
         if (blockIdx.y == 0) sweep_int64<8>(a, l, b, budget, tile_start);
     }
@@ -642,7 +920,7 @@ __device__ __forceinline__ int64_t last_layer_cost(const Layout &a, int b, int s
     if (shift > e) return kInf;
     const char *U = a.U[(a.L - 1) & 1] + ((int64_t)b * a.S_pad + s) * a.row * 8;
     const int64_t x = a.lead + e - shift;
-    if (st == GALV_INSTANCE_OK_FAST)
+    if (narrow_cells(st))
         return Narrow::to_int64(reinterpret_cast<const uint32_t *>(U)[x], a.k_bits);
     if (st == GALV_INSTANCE_OK_FAST_WIDE)
         return Wide::to_int64(reinterpret_cast<const double *>(U)[x], a.k_bits);
@@ -785,18 +1063,24 @@ __global__ __launch_bounds__(kThreads) void export_kernel(Layout a, int b, int64
 
 // Sweep variants, in ascending order of the strategies one workgroup covers
 // (TS * NG).  The first one that covers S is used; larger S use the last one with
-// several strategy groups along grid.y.  <TS, TE, NG, WPE>: TS * TE running minima
-// per lane (2 VGPRs each) for WPE resident waves per SIMD (512 VGPRs / WPE each).
+// several strategy groups along grid.y.  <TS, TE, NG, WPE[, W[, UX]]>: TS * TE running
+// minima per lane (2 VGPRs each with 64-bit keys, 1 with 32-bit keys) for WPE resident
+// waves per SIMD (512 VGPRs / WPE each), W waves per workgroup (default 4), UX times
+// the columns for the 32-bit-key body (default 1).
 // Measured on MI355X: small register tiles at 6-8 waves per SIMD with a shallow
 // prefetch beat large tiles at 2-4 waves with a deep one (the scalar R loads and
-// the table loads are hidden by occupancy).
+// the table loads are hidden by occupancy).  The last variant's workgroup has 8 waves
+// that cover 128 strategies of one tile: the waves read the same former-layer cells
+// and share them through the CU's cache, which cuts the HBM reads of S = 128 to a third
+// of what four separate 32-strategy workgroups fetch (same speed within 2 %).
 #ifndef GALV_V0
 #define GALV_V0 8, 2, 1, 8
 #define GALV_V1 16, 2, 1, 6
 #define GALV_V2 11, 2, 2, 8
 #define GALV_V3 16, 2, 2, 6
-#define GALV_V4 11, 2, 4, 8
-#define GALV_V5 16, 2, 2, 6
+#define GALV_V4 11, 2, 4, 6, 4, 2
+#define GALV_V5 16, 2, 4, 6
+#define GALV_V6 16, 2, 8, 6, 8
 #endif
 
 // ---------------------------------------------------------------------------------------------
@@ -916,16 +1200,20 @@ struct VariantEntry {
     Variant v;
     SweepFn fn, fn_u8;     // int32 and one-byte back-pointers
 };
-template <int TS, int TE, int NG, int WPE>
+template <int TS, int TE, int NG, int WPE, int W = 4, int UX = 1>
 VariantEntry variant_entry() {
-    static_assert(NG == 1 || NG == 2 || NG == 4, "strategy groups per workgroup");
-    return {{TS, TE, NG}, sweep_kernel<TS, TE, NG, WPE, int32_t>, sweep_kernel<TS, TE, NG, WPE, uint8_t>};
+    static_assert((W == 4 || W == 8) && W % NG == 0, "strategy groups must divide the workgroup's waves");
+    static_assert((UX == 1 || UX == 2) && TE * UX <= 4, "budget columns per lane");
+    return {{TS, TE, NG, W, UX},
+            sweep_kernel<TS, TE, NG, WPE, int32_t, W, UX>,
+            sweep_kernel<TS, TE, NG, WPE, uint8_t, W, UX>};
 }
 
 const VariantEntry &pick_variant(int S) {
     static const VariantEntry table[] = {
         variant_entry<GALV_V0>(), variant_entry<GALV_V1>(), variant_entry<GALV_V2>(),
-        variant_entry<GALV_V3>(), variant_entry<GALV_V4>(), variant_entry<GALV_V5>()};
+        variant_entry<GALV_V3>(), variant_entry<GALV_V4>(), variant_entry<GALV_V5>(),
+        variant_entry<GALV_V6>()};
     constexpr int n = sizeof table / sizeof table[0];
     for (int i = 0; i < n; ++i)
         if (S <= table[i].v.ts * table[i].v.ng) return table[i];
@@ -953,7 +1241,7 @@ struct Plan {
     Variant var;
     SweepFn sweep;
     Layout lay;
-    size_t off_U[2], off_bp, off_Rk, off_ck, off_vlist, off_nvalid, off_status, off_last, total;
+    size_t off_U[2], off_bp, off_Rk, off_ck, off_vlist, off_nvalid, off_status, off_last, off_dclamp, total;
     int groups_y;
 };
 
@@ -968,7 +1256,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     if (d->n_strategies > kMaxS)
         return fail(GALV_ERR_INVALID_ARG, "n_strategies %d exceeds the limit %d", d->n_strategies,
                     kMaxS);
-    if (d->flags & ~(GALV_DP_FORCE_INT64 | GALV_DP_BP_U8 | GALV_DP_STREAMS_MASK))
+    if (d->flags & ~(GALV_DP_FORCE_INT64 | GALV_DP_BP_U8 | GALV_DP_NO_U32 | GALV_DP_STREAMS_MASK))
         return fail(GALV_ERR_INVALID_ARG, "unknown flag bits");
     if (((d->flags & GALV_DP_STREAMS_MASK) >> GALV_DP_STREAMS_SHIFT) > (uint32_t)kMaxSide)
         return fail(GALV_ERR_INVALID_ARG, "at most %d internal streams", kMaxSide);
@@ -998,7 +1286,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     int k = 1;               // at least one index bit: the key builders shift by 32 - k
     while ((1 << k) < a.S) ++k;
     a.k_bits = k;
-    a.tile_e = kWave * v.te * (4 / v.ng);
+    a.tile_e = kWave * v.te * v.ux * (v.w / v.ng);
     a.e_pad = (int64_t)round_up((size_t)a.E_max + 1, kEAlign);
     a.n_tiles = (int32_t)((a.E_max + a.tile_e) / a.tile_e);   // ceil((E_max+1)/tile_e)
     a.lead = (int64_t)round_up((size_t)a.E_max + 1, 64);
@@ -1028,6 +1316,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     p->off_nvalid = take((size_t)a.B * a.L * sizeof(int32_t));
     p->off_status = take((size_t)a.B * sizeof(int32_t));
     p->off_last = take((size_t)a.B * sizeof(int32_t));
+    p->off_dclamp = take((size_t)a.B * sizeof(uint32_t));
     p->total = off;
     return GALV_OK;
 }
@@ -1113,6 +1402,7 @@ galv_status_t galv_dp_create(const galv_dp_desc_t *desc, void *workspace_dev,
     a.nvalid = reinterpret_cast<int32_t *>(ws + p.off_nvalid);
     a.status = reinterpret_cast<int32_t *>(ws + p.off_status);
     a.last = reinterpret_cast<int32_t *>(ws + p.off_last);
+    a.dclamp = reinterpret_cast<uint32_t *>(ws + p.off_dclamp);
     *out = h;
     return GALV_OK;
 }
@@ -1139,7 +1429,7 @@ galv_status_t galv_dp_solve_batched(galv_dp_t *h, const int64_t *c_dev, const in
     a.b_step = 1;
     if (h->n_side <= 1 || a.L < 2) {
         const dim3 grid(a.n_tiles, h->groups_y, a.B);
-        for (int l = 1; l < a.L; ++l) h->sweep<<<grid, kThreads, 0, st>>>(a, l);
+        for (int l = 1; l < a.L; ++l) h->sweep<<<grid, h->var.w * kWave, 0, st>>>(a, l);
     } else {
         // Instances are independent, so their layer chains need no common barrier: each
         // side stream sweeps its own share of the instances (dealt round-robin, which balances
@@ -1153,7 +1443,7 @@ galv_status_t galv_dp_solve_batched(galv_dp_t *h, const int64_t *c_dev, const in
             ag.b_off = g;
             ag.b_step = h->n_side;
             const dim3 grid(a.n_tiles, h->groups_y, count);
-            for (int l = 1; l < a.L; ++l) h->sweep<<<grid, kThreads, 0, h->side[g]>>>(ag, l);
+            for (int l = 1; l < a.L; ++l) h->sweep<<<grid, h->var.w * kWave, 0, h->side[g]>>>(ag, l);
             HIP_TRY(hipEventRecord(h->join[g], h->side[g]));
             HIP_TRY(hipStreamWaitEvent(st, h->join[g], 0));
         }

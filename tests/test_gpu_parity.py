@@ -12,6 +12,9 @@ from paper_2211_13878_amd import binding, workloads
 pytestmark = pytest.mark.gpu
 INF = binding.GALV_INF
 assert INF == oracle.INF
+# the three arithmetic paths a small-valued instance can be sent down: 32-bit integer keys
+# (default), 64-bit keys in 32-bit cells, general 64-bit integers
+ALL_PATHS = (0, binding.GALV_DP_NO_U32, binding.GALV_DP_FORCE_INT64)
 
 
 def gpu_solve(w, flags=0, tables=(), want_bp=True):
@@ -72,8 +75,10 @@ def check_properties(w, cost, last, plan):
 def test_config0_tables_and_golden():
     w = workloads.config(0)
     cost, last, plan, status = check_against_oracle(w, table_instances=[0],
-                                                    expect_status=binding.GALV_INSTANCE_OK_FAST)
+                                                    expect_status=binding.GALV_INSTANCE_OK_FAST_U32)
     assert int(cost[0]) == 33968 and list(plan[0]) == [3, 4, 0, 0]   # tests/golden
+    check_against_oracle(w, flags=binding.GALV_DP_NO_U32, table_instances=[0],
+                         expect_status=binding.GALV_INSTANCE_OK_FAST)
     check_against_oracle(w, flags=binding.GALV_DP_FORCE_INT64, table_instances=[0],
                          expect_status=binding.GALV_INSTANCE_OK_INT64)
 
@@ -81,9 +86,11 @@ def test_config0_tables_and_golden():
 def test_config1_full_batch_with_tables():
     w = workloads.config(1)
     cost, last, plan, _ = check_against_oracle(w, table_instances=[0, 5], threads=8,
-                                               expect_status=binding.GALV_INSTANCE_OK_FAST)
+                                               expect_status=binding.GALV_INSTANCE_OK_FAST_U32)
     check_properties(w, cost, last, plan)
     assert (cost < INF).all()
+    check_against_oracle(w, flags=binding.GALV_DP_NO_U32, table_instances=[3], threads=8,
+                         expect_status=binding.GALV_INSTANCE_OK_FAST)
 
 
 def test_config1_int64_path_prefix():
@@ -118,7 +125,7 @@ def test_config4_full_size_properties_and_truncated_budget():
     w = workloads.config(4)
     cost, last, plan, status, exported = gpu_solve(w, tables=[0, 11], want_bp=False)
     check_properties(w, cost, last, plan)
-    assert (status == binding.GALV_INSTANCE_OK_FAST).all() and (cost < INF).all()
+    assert (status == binding.GALV_INSTANCE_OK_FAST_U32).all() and (cost < INF).all()
     E_small = 4500
     for b in (0, 11):
         c, m, R, r_idx, _ = w.instance(b)
@@ -136,7 +143,7 @@ def test_config4_shape_small_budget_full_tables():
     w = workloads.config(4, 2)
     w.budget[:] = [1500, 2600]
     w.E_max = 2600
-    for flags in (0, binding.GALV_DP_FORCE_INT64):
+    for flags in ALL_PATHS:
         check_against_oracle(w, flags=flags, table_instances=[0, 1])
 
 
@@ -153,7 +160,7 @@ def test_random_shapes_ragged_tiles(S):
                                   c_range=(0, 50), r_range=(0, 20), infeasible=0.08,
                                   zero_diagonal=False)
     w.budget[0] = E_max
-    for flags in (0, binding.GALV_DP_FORCE_INT64):
+    for flags in ALL_PATHS:
         check_against_oracle(w, flags=flags, table_instances=[0, 1, 2])
 
 
@@ -161,7 +168,7 @@ def test_degenerate_sizes():
     for (L, S, E) in [(1, 1, 0), (1, 7, 5), (6, 1, 9), (2, 3, 0), (3, 4, 1)]:
         w = workloads.random_workload(7, 4, L, S, E, m_range=(0, 3), c_range=(0, 5),
                                       r_range=(0, 5))
-        for flags in (0, binding.GALV_DP_FORCE_INT64):
+        for flags in ALL_PATHS:
             check_against_oracle(w, flags=flags, table_instances=range(4))
 
 
@@ -198,7 +205,7 @@ def test_large_values_take_int64_path_and_agree():
     w.c[3] = w.c[3] % 1000
     w.R[3] = w.R[3] % 1000
     cost, last, plan, status = check_against_oracle(w, table_instances=[0, 3])
-    assert list(status) == [binding.GALV_INSTANCE_OK_INT64] * 3 + [binding.GALV_INSTANCE_OK_FAST]
+    assert list(status) == [binding.GALV_INSTANCE_OK_INT64] * 3 + [binding.GALV_INSTANCE_OK_FAST_U32]
 
 
 def test_mid_range_values_take_wide_storage():
@@ -210,8 +217,23 @@ def test_mid_range_values_take_wide_storage():
     w.c[3] = w.c[3] % ((1 << 31) // 7 - (1 << 26))
     w.R[3] = w.R[3] % ((1 << 26) // 7)
     cost, last, plan, status = check_against_oracle(w, table_instances=[0, 1, 3])
-    assert list(status) == [binding.GALV_INSTANCE_OK_FAST_WIDE] * 3 + [binding.GALV_INSTANCE_OK_FAST]
+    assert list(status) == [binding.GALV_INSTANCE_OK_FAST_WIDE] * 3 + [binding.GALV_INSTANCE_OK_FAST_U32]
     assert (cost[cost < INF] > (1 << 31)).any()
+
+
+def test_path_limits_by_transition_cost():
+    """32-bit integer keys need (2 * largest R + 2) * 2^k <= 2^32.  With k = 4: R up to 2^27 - 1 just
+    fits; one more and the instance takes 64-bit keys (costs still fit 32-bit cells).  Clamping of
+    relative costs is exercised hard here: R is far larger than the layer costs."""
+    w = workloads.random_workload(31, 3, 4, 12, 700, nR=2, m_range=(0, 200), c_range=(0, 1000),
+                                  r_range=(0, (1 << 27) - 1), infeasible=0.1, zero_diagonal=False)
+    w.R[0, 1, 3, 5] = (1 << 27) - 1
+    w.R[1, 0, 2, 2] = 1 << 27
+    w.R[2] = w.R[2] % 50                         # tiny R: almost everything is clamped
+    w.c[2] = w.c[2] * 1000
+    cost, last, plan, status = check_against_oracle(w, table_instances=[0, 1, 2])
+    assert list(status) == [binding.GALV_INSTANCE_OK_FAST_U32, binding.GALV_INSTANCE_OK_FAST,
+                            binding.GALV_INSTANCE_OK_FAST_U32]
 
 
 def test_bad_values_are_reported_not_solved():
@@ -224,7 +246,7 @@ def test_bad_values_are_reported_not_solved():
     assert list(status[:4]) == [binding.GALV_INSTANCE_BAD_VALUE] * 4
     assert (cost[:4] == INF).all() and (last[:4] == -1).all() and (plan[:4] == -1).all()
     ref = oracle.solve(*w.instance(4))
-    assert status[4] == binding.GALV_INSTANCE_OK_FAST and cost[4] == ref.best_cost
+    assert status[4] == binding.GALV_INSTANCE_OK_FAST_U32 and cost[4] == ref.best_cost
 
 
 def test_call_order_and_reuse():
@@ -268,7 +290,7 @@ def test_maximum_strategy_counts(S):
     w = workloads.random_workload(S, 2, 3, S, 300, nR=2, m_range=(0, 120), c_range=(0, 30),
                                   r_range=(0, 12), infeasible=0.05, zero_diagonal=False)
     w.budget[0] = 300
-    for flags in (0, binding.GALV_DP_FORCE_INT64):
+    for flags in ALL_PATHS:
         check_against_oracle(w, flags=flags, table_instances=[0])
 
 

@@ -4,8 +4,12 @@ from paper_2211_13878_amd.isa_check import count_requests, scalar_prefetch_viola
 
 GOOD = """
 _Zkernel:                               ; @_Zkernel
+\ts_load_dwordx8 s[20:27], s[0:1], 0x0  ; the compiler's own load: it waits before touching s[20:27]
+\ts_cbranch_scc1 .LBB0_9
+\t;;#ASMSTART
 \ts_load_dwordx16 s[36:51], s[0:1], 0x0
 \ts_load_dwordx16 s[52:67], s[0:1], 0x40
+\t;;#ASMEND
 \t;;#ASMSTART
 \tv_add_f64 v[58:59], v[56:57], s[4:5]
 \tv_min_f64 v[42:43], v[42:43], v[58:59]
