@@ -468,20 +468,26 @@ __device__ __forceinline__ void sweep_int64(const Layout &a, int l, int b, int b
 // strategy so that each needs only TE temporaries (left to itself the scheduler
 // hoists every add of a row above the minima and spills), with the adds ahead of
 // the minima so that no instruction waits on the one just issued.
+typedef double double8 __attribute__((ext_vector_type(8)));
+
+// `keep0`, `keep1` are the registers of the R group that is still being loaded while this
+// statement runs: naming them as (unused) inputs keeps their next use close, so the
+// register allocator has no reason to spill or move them while the load is in flight.
 template <int TE>
-__device__ __forceinline__ void minplus(double (&acc)[TE], const double (&v)[TE], double rk) {
+__device__ __forceinline__ void minplus(double (&acc)[TE], const double (&v)[TE], double rk,
+                                        const double8 &keep0, const double8 &keep1) {
     static_assert(TE == 1 || TE == 2 || TE == 4, "budget columns per lane");
     if constexpr (TE == 1) {
         double t0;
         asm("v_add_f64 %1, %2, %3\n\tv_min_f64 %0, %0, %1"
             : "+v"(acc[0]), "=&v"(t0)
-            : "v"(v[0]), "s"(rk));
+            : "v"(v[0]), "s"(rk), "s"(keep0), "s"(keep1));
     } else if constexpr (TE == 2) {
         double t0, t1;
         asm("v_add_f64 %2, %4, %6\n\tv_add_f64 %3, %5, %6\n\t"
             "v_min_f64 %0, %0, %2\n\tv_min_f64 %1, %1, %3"
             : "+v"(acc[0]), "+v"(acc[1]), "=&v"(t0), "=&v"(t1)
-            : "v"(v[0]), "v"(v[1]), "s"(rk));
+            : "v"(v[0]), "v"(v[1]), "s"(rk), "s"(keep0), "s"(keep1));
     } else {
         double t0, t1, t2, t3;
         asm("v_add_f64 %4, %8, %12\n\tv_add_f64 %5, %9, %12\n\t"
@@ -490,7 +496,7 @@ __device__ __forceinline__ void minplus(double (&acc)[TE], const double (&v)[TE]
             "v_min_f64 %2, %2, %6\n\tv_min_f64 %3, %3, %7"
             : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "=&v"(t0), "=&v"(t1),
               "=&v"(t2), "=&v"(t3)
-            : "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "s"(rk));
+            : "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "s"(rk), "s"(keep0), "s"(keep1));
     }
 }
 
@@ -503,7 +509,6 @@ __device__ __forceinline__ void minplus(double (&acc)[TE], const double (&v)[TE]
 // data would overwrite whatever it put there.  The build refuses such code: it
 // scans the produced assembly for any use of a destination register, any label or
 // any branch between a request and its wait (paper_2211_13878_amd/isa_check.py).
-typedef double double8 __attribute__((ext_vector_type(8)));
 template <int NCH>
 struct RGroup {
     double8 c[NCH];
@@ -603,7 +608,8 @@ __device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int bu
 #pragma unroll
                 for (int x = 0; x < kGroup; ++x)
                     if (gr * kGroup + x < TS)
-                        minplus<TE>(acc[gr * kGroup + x], key, buf[t & 1].c[x / 8][x % 8]);
+                        minplus<TE>(acc[gr * kGroup + x], key, buf[t & 1].c[x / 8][x % 8],
+                                    buf[(t + 1) & 1].c[0], buf[(t + 1) & 1].c[kChunks - 1]);
                 rgroup_await(buf[(t + 1) & 1]);
             }
         };
