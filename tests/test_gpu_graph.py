@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 
 @pytest.mark.parametrize("n_streams", [1, 3])
 def test_capture_and_replay(n_streams):
-    shapes = dict(B=6, L=10, S=22, E_max=1800)
+    shapes = dict(B=6, L=10, S=40, E_max=1800)     # the variant that stages cells in LDS
     ws = [workloads.random_workload(800 + i, shapes["B"], shapes["L"], shapes["S"], shapes["E_max"], nR=2,
                                     m_range=(0, 250), c_range=(0, 5000), r_range=(0, 900), infeasible=0.06)
           for i in range(4)]
