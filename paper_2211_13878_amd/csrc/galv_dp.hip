@@ -1262,7 +1262,7 @@ struct VariantEntry {
 };
 template <int TS, int TE, int NG, int WPE, int W = 4, int UX = 1, int STAGE = 0>
 VariantEntry variant_entry() {
-    static_assert((W == 4 || W == 8) && W % NG == 0, "strategy groups must divide the workgroup's waves");
+    static_assert((W == 3 || W == 4 || W == 6 || W == 8) && W % NG == 0, "strategy groups must divide the workgroup's waves");
     static_assert((UX == 1 || UX == 2) && TE * UX <= 4, "budget columns per lane");
     return {{TS, TE, NG, W, UX, STAGE},
             sweep_kernel<TS, TE, NG, WPE, int32_t, W, UX, STAGE != 0>,
