@@ -49,7 +49,7 @@ BYTES_PER_STATE = {3: 4 + 4 + 4, 0: 4 + 4 + 4, 2: 8 + 8 + 4, 1: 8 + 8 + 4}   # b
 
 # HBM bytes per sweep launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by the
 # same counter's reading for a 1 GiB copy (profiles/sweep_kernel_config<N>.md); None where not measured.
-MEASURED_TRAFFIC_BYTES = {3: 745155572, 4: 2669030866}
+MEASURED_TRAFFIC_BYTES = {3: 745100741, 4: 1771421157}
 
 
 def cpu_baseline(w, seconds_hint=20.0):

@@ -756,7 +756,7 @@ __device__ __forceinline__ void minplus_u32x2(uint32_t (&acc)[TE], const uint32_
 // sub-tile; every wave of the workgroup reaches the one barrier.
 extern __shared__ uint32_t lds_cells[];
 
-template <int TS, int TE, int NG, class BP, bool STAGE>
+template <int TS, int TE, int NG, class BP, int STAGE>
 __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int budget,
                                           int64_t tile_start) {
     static_assert(TS <= 16, "one scalar load fetches the R keys of a row");
@@ -824,10 +824,42 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int bud
             }
         }
         __syncthreads();
+        if constexpr (STAGE == 2) {
+            // The waves that share the columns also share the work on them: each reduces a
+            // part of the rows to partial column minima (kept behind the cells:
+            // [sub-tile][wave][column]) and, once the minima are known, turns its part of the
+            // cells into keys, so that the inner loop reads ready keys.
+            uint32_t *part = lds_cells + (int64_t)(blockDim.x / (kWave * NG)) * S * kCols +
+                             (int64_t)esub * NG * kCols;
+            if (in_budget) {
+                uint32_t pm[TE];
+#pragma unroll
+                for (int j = 0; j < TE; ++j) pm[j] = 0xffffffffu;
+                for (int i = g; i < n; i += NG)
+#pragma unroll
+                    for (int j = 0; j < TE; ++j) pm[j] = min(pm[j], mine[i * kCols + j * kWave + lane]);
+#pragma unroll
+                for (int j = 0; j < TE; ++j) part[g * kCols + j * kWave + lane] = pm[j];
+            }
+            __syncthreads();
+            if (in_budget) {
+#pragma unroll
+                for (int w = 0; w < NG; ++w)
+#pragma unroll
+                    for (int j = 0; j < TE; ++j) cmin[j] = min(cmin[j], part[w * kCols + j * kWave + lane]);
+                for (int i = g; i < n; i += NG)
+#pragma unroll
+                    for (int j = 0; j < TE; ++j) {
+                        uint32_t *c = &mine[i * kCols + j * kWave + lane];
+                        *c = min(*c - cmin[j], dmax) << k;
+                    }
+            }
+            __syncthreads();
+        }
         if (s0 >= a.S || !in_budget) return;
     }
 
-    if (n > 0 && STAGE) {
+    if (n > 0 && STAGE == 1) {
         for (int i = 0; i < n; ++i)
 #pragma unroll
             for (int j = 0; j < TE; ++j) cmin[j] = min(cmin[j], mine[i * kCols + j * kWave + lane]);
@@ -904,8 +936,8 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int bud
             uint32_t da[TE], db[TE];
 #pragma unroll
             for (int j = 0; j < TE; ++j) {
-                da[j] = min(va[q][j] - cmin[j], dmax) << k;
-                db[j] = min(vb[q][j] - cmin[j], dmax) << k;
+                da[j] = STAGE == 2 ? va[q][j] : min(va[q][j] - cmin[j], dmax) << k;
+                db[j] = STAGE == 2 ? vb[q][j] : min(vb[q][j] - cmin[j], dmax) << k;
             }
 #pragma unroll
             for (int s = 0; s < TS; ++s)
@@ -946,7 +978,7 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int bud
 
 // UX: the 32-bit-key body keeps half-size accumulators, so it may take UX (1 or 2) times
 // the budget columns per lane; the 64-bit-key bodies then cover the same tile in UX steps.
-template <int TS, int TE, int NG, int WPE, class BP, int W, int UX, bool STAGE>
+template <int TS, int TE, int NG, int WPE, class BP, int W, int UX, int STAGE>
 __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) {
     const int b = a.b_off + blockIdx.z * a.b_step;
     const int st = a.status[b];
@@ -1123,16 +1155,19 @@ __global__ __launch_bounds__(kThreads) void export_kernel(Layout a, int b, int64
 // minima per lane (2 VGPRs each with 64-bit keys, 1 with 32-bit keys) for WPE resident
 // waves per SIMD (512 VGPRs / WPE each), W waves per workgroup (default 4), UX times
 // the columns for the 32-bit-key body (default 1), STAGE = 1 to stage the former-layer
-// cells in LDS in that body (only where S is bounded by the variant: the LDS need is
-// S * 64 * TE * UX * 4 bytes per budget sub-tile).  Staging pays for S in 33..44
-// (3 % faster, HBM reads down from 2.1x to 1.2x the algorithmic ones) and not for the
-// smaller shapes.
+// cells in LDS in that body, 2 to share the column minima and the key conversion among
+// the workgroup's waves as well (only where S is bounded by the variant: the LDS need
+// is S * 64 * TE * UX * 4 bytes per budget sub-tile).  Measured: mode 1 pays for S in
+// 33..44 (3 % faster, HBM reads down from 2.1x to 1.2x the algorithmic ones; mode 2 is
+// 2 % slower there: two more barriers in a short-lived workgroup) and not for smaller
+// shapes; mode 2 pays for S = 128 (7 % faster: eight waves share the per-cell work of
+// 128 rows), where mode 1 alone does not.
 // Measured on MI355X: small register tiles at 6-8 waves per SIMD with a shallow
 // prefetch beat large tiles at 2-4 waves with a deep one (the scalar R loads and
-// the table loads are hidden by occupancy).  The last variant's workgroup has 8 waves
-// that cover 128 strategies of one tile: the waves read the same former-layer cells
-// and share them through the CU's cache, which cuts the HBM reads of S = 128 to a third
-// of what four separate 32-strategy workgroups fetch (same speed within 2 %).
+// the table loads are hidden by occupancy).  The last two variants' workgroups have 8
+// waves that cover 128 strategies of one tile: the waves read the same former-layer
+// cells, through LDS (S <= 128) or through the CU's cache (larger S), which cuts the HBM
+// reads of S = 128 to a third of what four separate 32-strategy workgroups fetch.
 #ifndef GALV_V0
 #define GALV_V0 8, 2, 1, 8
 #define GALV_V1 16, 2, 1, 6
@@ -1140,7 +1175,8 @@ __global__ __launch_bounds__(kThreads) void export_kernel(Layout a, int b, int64
 #define GALV_V3 16, 2, 2, 6
 #define GALV_V4 11, 2, 4, 8, 4, 1, 1
 #define GALV_V5 16, 2, 4, 6
-#define GALV_V6 16, 2, 8, 6, 8
+#define GALV_V6 16, 2, 8, 6, 8, 1, 2
+#define GALV_V7 16, 2, 8, 6, 8
 #endif
 
 // ---------------------------------------------------------------------------------------------
@@ -1265,15 +1301,15 @@ VariantEntry variant_entry() {
     static_assert((W == 3 || W == 4 || W == 6 || W == 8) && W % NG == 0, "strategy groups must divide the workgroup's waves");
     static_assert((UX == 1 || UX == 2) && TE * UX <= 4, "budget columns per lane");
     return {{TS, TE, NG, W, UX, STAGE},
-            sweep_kernel<TS, TE, NG, WPE, int32_t, W, UX, STAGE != 0>,
-            sweep_kernel<TS, TE, NG, WPE, uint8_t, W, UX, STAGE != 0>};
+            sweep_kernel<TS, TE, NG, WPE, int32_t, W, UX, STAGE>,
+            sweep_kernel<TS, TE, NG, WPE, uint8_t, W, UX, STAGE>};
 }
 
 const VariantEntry &pick_variant(int S) {
     static const VariantEntry table[] = {
         variant_entry<GALV_V0>(), variant_entry<GALV_V1>(), variant_entry<GALV_V2>(),
         variant_entry<GALV_V3>(), variant_entry<GALV_V4>(), variant_entry<GALV_V5>(),
-        variant_entry<GALV_V6>()};
+        variant_entry<GALV_V6>(), variant_entry<GALV_V7>()};
     constexpr int n = sizeof table / sizeof table[0];
     for (int i = 0; i < n; ++i)
         if (S <= table[i].v.ts * table[i].v.ng) return table[i];
@@ -1290,6 +1326,7 @@ struct galv_dp {
     size_t ws_bytes;
     int groups_y;      // grid.y of the sweep
     unsigned lds_bytes; // dynamic LDS of a sweep workgroup (staging variants only)
+    bool lds_allowed;   // the kernel has been told that it may use that much
     bool solved;
     int n_side;                    // > 1: the layer sweeps of disjoint instance ranges run on side streams
     hipStream_t side[kMaxSide];
@@ -1349,8 +1386,11 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     while ((1 << k) < a.S) ++k;
     a.k_bits = k;
     a.tile_e = kWave * v.te * v.ux * (v.w / v.ng);
-    p->lds_bytes = v.stage ? (unsigned)((size_t)(v.w / v.ng) * a.S * kWave * v.te * v.ux * sizeof(uint32_t)) : 0u;
-    if (p->lds_bytes > 64u * 1024u)
+    // staged cells [sub-tile][S][columns], then (mode 2) partial column minima [wave][columns]
+    p->lds_bytes = v.stage ? (unsigned)(((size_t)(v.w / v.ng) * a.S + (v.stage == 2 ? v.w : 0)) * kWave *
+                                        v.te * v.ux * sizeof(uint32_t))
+                           : 0u;
+    if (p->lds_bytes > 160u * 1024u)
         return fail(GALV_ERR_RANGE, "internal: staging variant needs %u bytes of LDS", p->lds_bytes);
     a.e_pad = (int64_t)round_up((size_t)a.E_max + 1, kEAlign);
     a.n_tiles = (int32_t)((a.E_max + a.tile_e) / a.tile_e);   // ceil((E_max+1)/tile_e)
@@ -1422,6 +1462,7 @@ galv_status_t galv_dp_create(const galv_dp_desc_t *desc, void *workspace_dev,
     h->ws_bytes = p.total;
     h->groups_y = p.groups_y;
     h->lds_bytes = p.lds_bytes;
+    h->lds_allowed = p.lds_bytes <= 64u * 1024u;
     h->solved = false;
     h->n_side = 0;
     int n = (int)((desc->flags & GALV_DP_STREAMS_MASK) >> GALV_DP_STREAMS_SHIFT);
@@ -1491,6 +1532,11 @@ galv_status_t galv_dp_solve_batched(galv_dp_t *h, const int64_t *c_dev, const in
 
     prep_kernel<<<a.B, kThreads, 0, st>>>(a, h->desc.flags);
     init_kernel<<<dim3((unsigned)((a.row + kThreads - 1) / kThreads), a.S, a.B), kThreads, 0, st>>>(a);
+    if (!h->lds_allowed) {     // more than the default 64 KB of dynamic LDS: say so once
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(h->sweep),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_bytes));
+        h->lds_allowed = true;
+    }
     a.b_off = 0;
     a.b_step = 1;
     if (h->n_side <= 1 || a.L < 2) {
