@@ -289,6 +289,10 @@ def main():
                         "figure that a kernel trace shows directly (ALU fraction)",
                 "single_stream": single, "alu": alu_obj, "hbm": hbm_obj}
 
+    kinds = {3: "u32", 0: "f64", 2: "f64", 1: "int64"}
+    used = sorted({kinds[int(st)] for st in status if int(st) in kinds})
+    dtype = ("+".join(used) or "none") + " (exact integer keys; int64 costs in, int64 costs out)"
+
     out = {
         "metric": "dp_cell_updates_per_sec",
         "value": nominal / (ms_per_step * 1e-3),
@@ -296,7 +300,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int64" if args.force_int64 else "f64 (exact integer keys; int64 in, int64 out)",
+        "dtype": dtype,
         "data": "synthetic",
         "config": {"workload": f"config {args.config} '{w.name}': B={w.B} L={w.L} S={w.S} "
                                f"E_max={w.E_max} budgets {int(w.budget.min())}..{int(w.budget.max())}",
