@@ -133,8 +133,9 @@ galv_status_t galv_dp_solve_batched(galv_dp_t *h, const int64_t *c_dev, const in
                                     int32_t *best_last_dev, void *stream);
 
 /*
- * Recover the optimal plan of every instance of the last solve by walking the
- * back-pointers from (L-1, budget[b], best_last[b]) to layer 0.
+ * Recover the optimal plan of every instance of the last solve (the per-layer strategies
+ * that the search of section 3.3 returns besides the minimum time cost: Algorithm 1's
+ * output) by walking the back-pointers from (L-1, budget[b], best_last[b]) to layer 0.
  *   plan_dev [B][L] out int32  strategy index per layer; all -1 when no plan fits.
  * Must be enqueued on the same stream as (or ordered after) the solve.
  */

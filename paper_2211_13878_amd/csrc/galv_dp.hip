@@ -115,6 +115,7 @@ struct Layout {
     uint32_t *dclamp;     // 32-bit-key path: largest R + 1, the clamp of relative costs  [B]
     int32_t *status;      // per instance        [B]
     int32_t *last;        // best last strategy  [B]
+    int32_t *lead_mode;   // whose infinity leads the rows hold: 1 narrow, 2 wide, 0 none  [B]
     const int64_t *c;
     const int32_t *m;
     const int64_t *R;
@@ -375,7 +376,12 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
 // Layer 0: U_0[e'][s] = c(0,s) for every e' (the shift by m(0,s) is applied by
 // whoever reads it), and the infinity lead in front of both rolling rows of the
 // strategy.  Grid: (row cells / 256, S, B).
-__global__ __launch_bounds__(kThreads) void init_kernel(Layout a) {
+//
+// The leads never change while an instance keeps its storage mode, and no sweep
+// writes into them, so only the first solve of a handle (fresh != 0) and a solve
+// that finds another mode than the one recorded in lead_mode[b] write them;
+// final_kernel records the mode once the solve is through.
+__global__ __launch_bounds__(kThreads) void init_kernel(Layout a, int fresh) {
     const int b = blockIdx.z, s = blockIdx.y;
     const int st = a.status[b];
     if (st < 0) return;
@@ -387,13 +393,16 @@ __global__ __launch_bounds__(kThreads) void init_kernel(Layout a) {
             reinterpret_cast<int64_t *>(a.U[0] + base)[x] = a.c[((int64_t)b * a.L) * a.S + s];
         return;
     }
+    const bool leads = fresh || a.lead_mode[b] != (narrow_cells(st) ? 1 : 2);
     const uint64_t cs = a.ck[((int64_t)b * a.L) * a.S_pad + s];
     if (narrow_cells(st)) {
         uint32_t *u0 = reinterpret_cast<uint32_t *>(a.U[0] + base);
         uint32_t *u1 = reinterpret_cast<uint32_t *>(a.U[1] + base);
         if (x < a.lead) {
-            u0[x] = Narrow::infinity();
-            u1[x] = Narrow::infinity();
+            if (leads) {
+                u0[x] = Narrow::infinity();
+                u1[x] = Narrow::infinity();
+            }
         } else {
             u0[x] = Narrow::first_layer(cs);
         }
@@ -401,8 +410,10 @@ __global__ __launch_bounds__(kThreads) void init_kernel(Layout a) {
         double *u0 = reinterpret_cast<double *>(a.U[0] + base);
         double *u1 = reinterpret_cast<double *>(a.U[1] + base);
         if (x < a.lead) {
-            u0[x] = Wide::infinity();
-            u1[x] = Wide::infinity();
+            if (leads) {
+                u0[x] = Wide::infinity();
+                u1[x] = Wide::infinity();
+            }
         } else {
             u0[x] = Wide::first_layer(cs);
         }
@@ -1038,6 +1049,8 @@ __global__ __launch_bounds__(kThreads) void final_kernel(Layout a, int64_t *best
         best_cost[b] = opt;
         best_last[b] = last;
         a.last[b] = last;
+        // every block of init_kernel has long finished: safe to record what the leads hold
+        a.lead_mode[b] = st < 0 || st == GALV_INSTANCE_OK_INT64 ? 0 : (narrow_cells(st) ? 1 : 2);
     }
 }
 
@@ -1328,6 +1341,7 @@ struct galv_dp {
     unsigned lds_bytes; // dynamic LDS of a sweep workgroup (staging variants only)
     bool lds_allowed;   // the kernel has been told that it may use that much
     bool solved;
+    bool fresh;         // no solve has run over this workspace yet: the infinity leads are unwritten
     int n_side;                    // > 1: the layer sweeps of disjoint instance ranges run on side streams
     hipStream_t side[kMaxSide];
     hipEvent_t fork, join[kMaxSide];
@@ -1339,7 +1353,8 @@ struct Plan {
     Variant var;
     SweepFn sweep;
     Layout lay;
-    size_t off_U[2], off_bp, off_Rk, off_ck, off_vlist, off_nvalid, off_status, off_last, off_dclamp, total;
+    size_t off_U[2], off_bp, off_Rk, off_ck, off_vlist, off_nvalid, off_status, off_last, off_dclamp,
+        off_lead_mode, total;
     int groups_y;
     unsigned lds_bytes;
 };
@@ -1422,7 +1437,87 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     p->off_status = take((size_t)a.B * sizeof(int32_t));
     p->off_last = take((size_t)a.B * sizeof(int32_t));
     p->off_dclamp = take((size_t)a.B * sizeof(uint32_t));
+    p->off_lead_mode = take((size_t)a.B * sizeof(int32_t));
     p->total = off;
+    return GALV_OK;
+}
+
+// Point a layout's table pointers into a workspace laid out by make_plan.
+void bind_workspace(Layout &a, const Plan &p, char *ws) {
+    a.U[0] = ws + p.off_U[0];
+    a.U[1] = ws + p.off_U[1];
+    a.bp = ws + p.off_bp;
+    a.Rk = reinterpret_cast<double *>(ws + p.off_Rk);
+    a.ck = reinterpret_cast<uint64_t *>(ws + p.off_ck);
+    a.vlist = reinterpret_cast<uint64_t *>(ws + p.off_vlist);
+    a.nvalid = reinterpret_cast<int32_t *>(ws + p.off_nvalid);
+    a.status = reinterpret_cast<int32_t *>(ws + p.off_status);
+    a.last = reinterpret_cast<int32_t *>(ws + p.off_last);
+    a.dclamp = reinterpret_cast<uint32_t *>(ws + p.off_dclamp);
+    a.lead_mode = reinterpret_cast<int32_t *>(ws + p.off_lead_mode);
+}
+
+// Enqueue one whole solve (preparation, layer 0, the L-1 sweeps, final minimum) of handle h on
+// stream st.  Shared by every entry point that solves.
+galv_status_t enqueue_solve(galv_dp *h, const int64_t *c_dev, const int32_t *m_dev,
+                            const int64_t *R_dev, const int32_t *r_idx_dev,
+                            const int32_t *budget_dev, int64_t *best_cost_dev,
+                            int32_t *best_last_dev, hipStream_t st) {
+    Layout &a = h->lay;
+    a.c = c_dev;
+    a.m = m_dev;
+    a.R = R_dev;
+    a.r_idx = r_idx_dev;
+    a.budget = budget_dev;
+    h->solved = false;
+
+    if (!h->lds_allowed) {     // more than the default 64 KB of dynamic LDS: say so before any launch
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(h->sweep),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_bytes));
+        h->lds_allowed = true;
+    }
+    prep_kernel<<<a.B, kThreads, 0, st>>>(a, h->desc.flags);
+    init_kernel<<<dim3((unsigned)((a.row + kThreads - 1) / kThreads), a.S, a.B), kThreads, 0, st>>>(
+        a, h->fresh ? 1 : 0);
+    a.b_off = 0;
+    a.b_step = 1;
+    if (h->n_side <= 1 || a.L < 2) {
+        const dim3 grid(a.n_tiles, h->groups_y, a.B);
+        for (int l = 1; l < a.L; ++l) h->sweep<<<grid, h->var.w * kWave, h->lds_bytes, st>>>(a, l);
+    } else {
+        // Instances are independent, so their layer chains need no common barrier: each
+        // side stream sweeps its own share of the instances (dealt round-robin, which balances
+        // unequal budgets) and the shares overlap freely.
+        HIP_TRY(hipEventRecord(h->fork, st));
+        // A failure after the fork must not leave side streams running behind the caller's
+        // back: whatever was started is still joined into `st` before the error is returned.
+        hipError_t err = hipSuccess;
+        for (int g = 0; g < h->n_side && err == hipSuccess; ++g) {
+            const int count = (a.B - g + h->n_side - 1) / h->n_side;    // instances g, g + n, g + 2n, ...
+            if (count <= 0) continue;
+            err = hipStreamWaitEvent(h->side[g], h->fork, 0);
+            if (err != hipSuccess) break;                 // nothing enqueued on this side stream
+            Layout ag = a;
+            ag.b_off = g;
+            ag.b_step = h->n_side;
+            const dim3 grid(a.n_tiles, h->groups_y, count);
+            for (int l = 1; l < a.L; ++l) h->sweep<<<grid, h->var.w * kWave, h->lds_bytes, h->side[g]>>>(ag, l);
+            err = hipEventRecord(h->join[g], h->side[g]);
+            const hipError_t e2 = err == hipSuccess ? hipStreamWaitEvent(st, h->join[g], 0) : err;
+            if (e2 != hipSuccess) {
+                // could not order `st` after this side stream: wait for it on the host instead
+                (void)hipStreamSynchronize(h->side[g]);
+                err = e2;
+            }
+        }
+        if (err != hipSuccess)
+            return fail(GALV_ERR_HIP, "forking the layer sweeps over internal streams failed: %s",
+                        hipGetErrorString(err));
+    }
+    final_kernel<<<a.B, kThreads, 0, st>>>(a, best_cost_dev, best_last_dev);
+    HIP_TRY(hipGetLastError());
+    h->solved = true;
+    h->fresh = false;
     return GALV_OK;
 }
 
@@ -1464,6 +1559,7 @@ galv_status_t galv_dp_create(const galv_dp_desc_t *desc, void *workspace_dev,
     h->lds_bytes = p.lds_bytes;
     h->lds_allowed = p.lds_bytes <= 64u * 1024u;
     h->solved = false;
+    h->fresh = true;
     h->n_side = 0;
     int n = (int)((desc->flags & GALV_DP_STREAMS_MASK) >> GALV_DP_STREAMS_SHIFT);
     if (n == 0) {
@@ -1498,18 +1594,7 @@ galv_status_t galv_dp_create(const galv_dp_desc_t *desc, void *workspace_dev,
         }
         h->n_side = n;
     }
-    char *ws = static_cast<char *>(workspace_dev);
-    Layout &a = h->lay;
-    a.U[0] = ws + p.off_U[0];
-    a.U[1] = ws + p.off_U[1];
-    a.bp = ws + p.off_bp;
-    a.Rk = reinterpret_cast<double *>(ws + p.off_Rk);
-    a.ck = reinterpret_cast<uint64_t *>(ws + p.off_ck);
-    a.vlist = reinterpret_cast<uint64_t *>(ws + p.off_vlist);
-    a.nvalid = reinterpret_cast<int32_t *>(ws + p.off_nvalid);
-    a.status = reinterpret_cast<int32_t *>(ws + p.off_status);
-    a.last = reinterpret_cast<int32_t *>(ws + p.off_last);
-    a.dclamp = reinterpret_cast<uint32_t *>(ws + p.off_dclamp);
+    bind_workspace(h->lay, p, static_cast<char *>(workspace_dev));
     *out = h;
     return GALV_OK;
 }
@@ -1521,49 +1606,8 @@ galv_status_t galv_dp_solve_batched(galv_dp_t *h, const int64_t *c_dev, const in
     if (!h) return fail(GALV_ERR_INVALID_ARG, "handle is NULL");
     if (!c_dev || !m_dev || !R_dev || !budget_dev || !best_cost_dev || !best_last_dev)
         return fail(GALV_ERR_INVALID_ARG, "a required device pointer is NULL");
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    Layout &a = h->lay;
-    a.c = c_dev;
-    a.m = m_dev;
-    a.R = R_dev;
-    a.r_idx = r_idx_dev;
-    a.budget = budget_dev;
-    h->solved = false;
-
-    prep_kernel<<<a.B, kThreads, 0, st>>>(a, h->desc.flags);
-    init_kernel<<<dim3((unsigned)((a.row + kThreads - 1) / kThreads), a.S, a.B), kThreads, 0, st>>>(a);
-    if (!h->lds_allowed) {     // more than the default 64 KB of dynamic LDS: say so once
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(h->sweep),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_bytes));
-        h->lds_allowed = true;
-    }
-    a.b_off = 0;
-    a.b_step = 1;
-    if (h->n_side <= 1 || a.L < 2) {
-        const dim3 grid(a.n_tiles, h->groups_y, a.B);
-        for (int l = 1; l < a.L; ++l) h->sweep<<<grid, h->var.w * kWave, h->lds_bytes, st>>>(a, l);
-    } else {
-        // Instances are independent, so their layer chains need no common barrier: each
-        // side stream sweeps its own share of the instances (dealt round-robin, which balances
-        // unequal budgets) and the shares overlap freely.
-        HIP_TRY(hipEventRecord(h->fork, st));
-        for (int g = 0; g < h->n_side; ++g) {
-            const int count = (a.B - g + h->n_side - 1) / h->n_side;    // instances g, g + n, g + 2n, ...
-            if (count <= 0) continue;
-            HIP_TRY(hipStreamWaitEvent(h->side[g], h->fork, 0));
-            Layout ag = a;
-            ag.b_off = g;
-            ag.b_step = h->n_side;
-            const dim3 grid(a.n_tiles, h->groups_y, count);
-            for (int l = 1; l < a.L; ++l) h->sweep<<<grid, h->var.w * kWave, h->lds_bytes, h->side[g]>>>(ag, l);
-            HIP_TRY(hipEventRecord(h->join[g], h->side[g]));
-            HIP_TRY(hipStreamWaitEvent(st, h->join[g], 0));
-        }
-    }
-    final_kernel<<<a.B, kThreads, 0, st>>>(a, best_cost_dev, best_last_dev);
-    HIP_TRY(hipGetLastError());
-    h->solved = true;
-    return GALV_OK;
+    return enqueue_solve(h, c_dev, m_dev, R_dev, r_idx_dev, budget_dev, best_cost_dev, best_last_dev,
+                         static_cast<hipStream_t>(stream));
 }
 
 galv_status_t galv_dp_backtrack(galv_dp_t *h, int32_t *plan_dev, void *stream) {
