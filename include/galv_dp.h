@@ -142,6 +142,29 @@ galv_status_t galv_dp_solve_batched(galv_dp_t *h, const int64_t *c_dev, const in
 galv_status_t galv_dp_backtrack(galv_dp_t *h, int32_t *plan_dev, void *stream);
 
 /*
+ * Solve and backtrack in one call that ALLOCATES NOTHING, for callers that cannot allocate
+ * device memory or create a handle: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same results as galv_dp_create + galv_dp_solve_batched +
+ * galv_dp_backtrack, same kernels; the workspace is a fixed array of GALV_DP_STATIC_BYTES
+ * inside the library's code object (one copy per GPU, held until the process ends), found
+ * once per device through hipGetSymbolAddress.
+ *   desc       shape and flags as for galv_dp_create; GALV_DP_STREAMS must be 0 or 1 (all
+ *              work runs on `stream`).  A shape whose galv_dp_workspace_bytes exceeds
+ *              GALV_DP_STATIC_BYTES is refused with GALV_ERR_WORKSPACE and nothing is enqueued.
+ *   inputs and best_cost_dev / best_last_dev as for galv_dp_solve_batched, plan_dev [B][L]
+ *              as for galv_dp_backtrack; all must stay alive until `stream` has passed the call.
+ * No hipMalloc / hipFree, no stream or event creation, no host synchronisation.  Every call
+ * on a GPU uses that GPU's one array, which keeps the previous call's contents (the solve
+ * rewrites all it reads): calls that overlap in time on one GPU, on whatever streams, race.
+ */
+#define GALV_DP_STATIC_BYTES (32u << 20)
+galv_status_t galv_dp_solve_static(const galv_dp_desc_t *desc, const int64_t *c_dev,
+                                   const int32_t *m_dev, const int64_t *R_dev,
+                                   const int32_t *r_idx_dev, const int32_t *budget_dev,
+                                   int64_t *best_cost_dev, int32_t *best_last_dev, int32_t *plan_dev,
+                                   void *stream);
+
+/*
  * All budgets at once.  The table has "at most e" semantics (the optimal-substructure
  * argument of section 3.3: the optimum of a smaller budget E' <= E is a sub-problem
  * of the same table), so one solve at budget[b] answers every smaller budget, as

@@ -34,7 +34,7 @@ GALV_INSTANCE_OK_FAST, GALV_INSTANCE_OK_INT64, GALV_INSTANCE_OK_FAST_WIDE, GALV_
 GALV_INSTANCE_BAD_VALUE = -1
 
 EXPORTS = ("galv_dp_workspace_bytes", "galv_dp_create", "galv_dp_solve_batched",
-           "galv_dp_backtrack", "galv_dp_best_per_budget", "galv_dp_backtrack_queries",
+           "galv_dp_backtrack", "galv_dp_solve_static", "galv_dp_best_per_budget", "galv_dp_backtrack_queries",
            "galv_dp_export_tables", "galv_dp_get_status", "galv_alg1_reduce",
            "galv_dp_coarsen", "galv_dp_expand_plan",
            "galv_dp_destroy", "galv_dp_last_error")
@@ -69,6 +69,7 @@ def load_library() -> ctypes.CDLL:
         lib.galv_dp_create.argtypes = [ctypes.POINTER(Desc), vp, ctypes.c_size_t, ctypes.POINTER(vp)]
         lib.galv_dp_solve_batched.argtypes = [vp] * 9
         lib.galv_dp_backtrack.argtypes = [vp, vp, vp]
+        lib.galv_dp_solve_static.argtypes = [ctypes.POINTER(Desc)] + [vp] * 9
         lib.galv_dp_best_per_budget.argtypes = [vp, vp, vp, vp]
         lib.galv_dp_backtrack_queries.argtypes = [vp, i32, vp, vp, vp, vp, vp]
         lib.galv_dp_export_tables.argtypes = [vp, i32, vp, vp, vp]
@@ -137,6 +138,18 @@ def galv_dp_solve_batched(h, c, m, R, r_idx, budget, best_cost, best_last, strea
 
 def galv_dp_backtrack(h, plan, stream=None):
     _check(load_library().galv_dp_backtrack(h, _dev_ptr(plan, torch.int32), _stream_ptr(stream)))
+
+
+GALV_DP_STATIC_BYTES = 32 << 20
+
+
+def galv_dp_solve_static(desc, c, m, R, r_idx, budget, best_cost, best_last, plan, stream=None):
+    """Solve + backtrack over the library's fixed workspace; allocates nothing."""
+    _check(load_library().galv_dp_solve_static(
+        ctypes.byref(desc), _dev_ptr(c, torch.int64), _dev_ptr(m, torch.int32), _dev_ptr(R, torch.int64),
+        _dev_ptr(r_idx, torch.int32, allow_none=True), _dev_ptr(budget, torch.int32),
+        _dev_ptr(best_cost, torch.int64), _dev_ptr(best_last, torch.int32), _dev_ptr(plan, torch.int32),
+        _stream_ptr(stream)))
 
 
 def galv_dp_best_per_budget(h, best_cost, best_last, stream=None):

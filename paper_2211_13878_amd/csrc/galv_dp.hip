@@ -44,10 +44,17 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <type_traits>
 
 #include "../../include/galv_dp.h"
+
+// Workspace of galv_dp_solve_static, the entry point that allocates nothing: it lives in the
+// code object, one copy per GPU for as long as the process runs.  Host code never uses this
+// name as an address; it asks the runtime for the device address once per device (see
+// static_scratch()).
+static __device__ __align__(256) unsigned char scratch[GALV_DP_STATIC_BYTES];
 
 namespace {
 
@@ -1521,6 +1528,29 @@ galv_status_t enqueue_solve(galv_dp *h, const int64_t *c_dev, const int32_t *m_d
     return GALV_OK;
 }
 
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];       // device address of `scratch` on each GPU, once known
+std::mutex g_scratch_mutex;
+
+// Device address of the current GPU's copy of `scratch`, looked up on the first call per device.
+galv_status_t static_scratch(void **out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices)
+        return fail(GALV_ERR_RANGE, "device ordinal %d is outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || reinterpret_cast<uintptr_t>(ptr) % 256 != 0)
+            return fail(GALV_ERR_HIP, "the static workspace has no usable device address (%p)", ptr);
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return GALV_OK;
+}
+
+
 }  // namespace
 
 extern "C" {
@@ -1617,6 +1647,50 @@ galv_status_t galv_dp_backtrack(galv_dp_t *h, int32_t *plan_dev, void *stream) {
     const Layout &a = h->lay;
     backtrack_kernel<<<(a.B + kWave - 1) / kWave, kWave, 0, static_cast<hipStream_t>(stream)>>>(
         a, plan_dev);
+    HIP_TRY(hipGetLastError());
+    return GALV_OK;
+}
+
+galv_status_t galv_dp_solve_static(const galv_dp_desc_t *desc, const int64_t *c_dev,
+                                   const int32_t *m_dev, const int64_t *R_dev,
+                                   const int32_t *r_idx_dev, const int32_t *budget_dev,
+                                   int64_t *best_cost_dev, int32_t *best_last_dev, int32_t *plan_dev,
+                                   void *stream) {
+    Plan p;
+    galv_status_t rc = make_plan(desc, &p);
+    if (rc != GALV_OK) return rc;
+    if (((desc->flags & GALV_DP_STREAMS_MASK) >> GALV_DP_STREAMS_SHIFT) > 1u)
+        return fail(GALV_ERR_INVALID_ARG, "galv_dp_solve_static runs on the caller's stream only "
+                                          "(GALV_DP_STREAMS must be 0 or 1)");
+    if (p.total > (size_t)GALV_DP_STATIC_BYTES)
+        return fail(GALV_ERR_WORKSPACE,
+                    "this shape needs %zu bytes of workspace; galv_dp_solve_static holds %zu "
+                    "(use galv_dp_create with a workspace of your own)",
+                    p.total, (size_t)GALV_DP_STATIC_BYTES);
+    if (!c_dev || !m_dev || !R_dev || !budget_dev || !best_cost_dev || !best_last_dev || !plan_dev)
+        return fail(GALV_ERR_INVALID_ARG, "a required device pointer is NULL");
+    void *ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc != GALV_OK) return rc;
+
+    // A handle on the stack: host memory only, no internal streams, nothing to destroy.
+    galv_dp h;
+    h.desc = *desc;
+    h.var = p.var;
+    h.sweep = p.sweep;
+    h.lay = p.lay;
+    h.ws_bytes = p.total;
+    h.groups_y = p.groups_y;
+    h.lds_bytes = p.lds_bytes;
+    h.lds_allowed = p.lds_bytes <= 64u * 1024u;
+    h.solved = false;
+    h.fresh = true;            // the array keeps the last call's contents: write the leads anew
+    h.n_side = 0;
+    bind_workspace(h.lay, p, static_cast<char *>(ws));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = enqueue_solve(&h, c_dev, m_dev, R_dev, r_idx_dev, budget_dev, best_cost_dev, best_last_dev, st);
+    if (rc != GALV_OK) return rc;
+    backtrack_kernel<<<(h.lay.B + kWave - 1) / kWave, kWave, 0, st>>>(h.lay, plan_dev);
     HIP_TRY(hipGetLastError());
     return GALV_OK;
 }
