@@ -5,26 +5,32 @@ One "step" is one pass of the whole hot path over one batch of synthetic search
 instances that already live in HBM: galv_dp_solve_batched (preparation, layer 0,
 the L-1 layer sweeps, final minimum) followed by galv_dp_backtrack.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config N] [--no-cpu-baseline]
                     [--streams N] [--bp-u8] [--graph] [--no-extra-legs] [--coarsen FUSE,GRAN]
 
-Prints ONE JSON line.  `value` is DP cell-updates/s with the metric's nominal
-count sum_b L * E_b * S^2 per batch, in the library's default configuration
-(int32 back-pointers, internal streams chosen from the shape); searches/s and
-the exact candidate rate are reported beside it.
+Prints ONE JSON line.  By default both target configurations are timed, 4 (the
+largest that one GPU holds: the headline `value`, `ms_per_step`, `roofline` and
+`cpu_baseline`) and 3; `per_config` carries the full record of each.  `--config N`
+times that configuration alone.  `value` is DP cell-updates/s with the metric's
+nominal count sum_b L * E_b * S^2 per batch, in the library's default
+configuration (int32 back-pointers, internal streams chosen from the shape);
+searches/s and the exact candidate rate are reported beside it.
 
 `roofline` is for the layer-sweep kernel (the only kernel that matters: > 98 %
 of the time): exact min-plus candidates of one layer times the VALU
 lane-operations each one needs on its instance's arithmetic path (1.5 with
 32-bit keys: two adds and one three-way minimum per two candidates; 2 with
-64-bit keys: one add, one minimum), divided by the sweep time per layer (events on the caller's stream around the solve, / (L-1)),
-against the chip's VALU issue peak of 256 CUs x 64 lanes x 2.4 GHz = 39.3 T
-lane-ops/s.  With internal streams a layer is several overlapping launches;
+64-bit keys: one add, one minimum), divided by the sweep time per layer (events
+on the caller's stream around the solve, / (L-1)), against the chip's VALU issue
+peak of 256 CUs x 64 lanes x 2.4 GHz = 39.3 T lane-ops/s.  With internal streams
+a layer is several overlapping launches, so that figure rests on event timing;
 `roofline.single_stream` is a second timed leg with one launch per layer, the
-figure a kernel trace of `--streams 1` shows directly.  `variant_bp_u8` is a
-third leg with one-byte back-pointers (same results, 9 instead of 12 B/state).
-`cpu_baseline` times the serial CPU oracle (test infrastructure, never tuned)
-on a sample of instances of the same workload.
+kernel's own figure, which a kernel trace of `--streams 1` shows directly.
+`variant_bp_u8` is a third leg with one-byte back-pointers (same results, 9
+instead of 12 B/state).
+`cpu_baseline` times the serial CPU oracle (test infrastructure, never tuned) on a
+bounded sample of the same workload: one instance on one thread, and one instance
+per thread on the host cores this process may use.
 """
 from __future__ import annotations
 
@@ -52,25 +58,47 @@ BYTES_PER_STATE = {3: 4 + 4 + 4, 0: 4 + 4 + 4, 2: 8 + 8 + 4, 1: 8 + 8 + 4}   # b
 MEASURED_TRAFFIC_BYTES = {3: 745100741, 4: 1771421157}
 
 
-def cpu_baseline(w, seconds_hint=20.0):
-    """Oracle wall time on a bounded sample of the workload's instances."""
+def cpu_baseline(w):
+    """Oracle wall time on a bounded sample of the workload's instances: one instance on one
+    thread (per-core rate), then one instance per thread side by side (whole-host rate).
+    An instance whose full budget would take the oracle minutes is solved at a truncated
+    budget (same layers, strategies and values; the work per budget column does not depend on
+    the column), and the sample says so."""
+    import copy
+
     import oracle
     oracle.build()
-    threads = max(1, min(8, os.cpu_count() or 1))
-    # spread the sample over the batch (budgets differ across instances)
+    host = os.cpu_count() or 1
+    try:
+        host = min(host, len(os.sched_getaffinity(0)))
+    except (AttributeError, OSError):
+        pass
+    # a GPU box gives one GPU's job a share of 16 cores whatever the core count it shows
+    threads = max(1, min(host, 16, w.B))
+    per_core = 2.0e9                                   # rough oracle rate used only to size the sample
+    cap = int(15.0 * per_core / (w.L * w.S * w.S))     # budget columns one thread sweeps in ~15 s
+    ws = copy.copy(w)
+    ws.budget = w.budget.copy()
+    truncated = bool((ws.budget > cap).any())
+    ws.budget[ws.budget > cap] = cap
     ids = sorted({int(round(i * (w.B - 1) / max(1, threads - 1))) for i in range(threads)})
-    per_inst = [w.L * int(w.budget[b]) * w.S * w.S for b in ids]
-    # keep the sample near the time hint assuming ~0.7e9 updates/s per core
-    while len(ids) > 1 and max(per_inst) / 0.7e9 > seconds_hint:
-        drop = per_inst.index(max(per_inst))
-        ids.pop(drop); per_inst.pop(drop)
+    updates = lambda b: w.L * int(ws.budget[b]) * w.S * w.S
+    what = (f"budgets truncated to {cap} of {int(w.budget.max())} columns" if truncated
+            else "full budget each")
+    one = ids[len(ids) // 2]
     t0 = time.perf_counter()
-    oracle.solve_workload(w, ids, threads=len(ids))
+    oracle.solve_workload(ws, [one], threads=1)
+    dt1 = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oracle.solve_workload(ws, ids, threads=len(ids))
     dt = time.perf_counter() - t0
-    return {"value": sum(per_inst) / dt, "unit": "cell-updates/s", "cores": len(ids),
-            "kind": "oracle", "seconds": round(dt, 3),
+    return {"value": sum(updates(b) for b in ids) / dt, "unit": "cell-updates/s", "cores": len(ids),
+            "host_cpu_count": os.cpu_count(), "kind": "oracle", "seconds": round(dt, 3),
             "sample": f"{len(ids)} of {w.B} instances of '{w.name}' (ids {ids}), one per thread, "
-                      f"full L and budget each"}
+                      f"all L layers, {what}",
+            "single_thread": {"value": updates(one) / dt1, "unit": "cell-updates/s", "cores": 1,
+                              "seconds": round(dt1, 3),
+                              "sample": f"instance {one} of '{w.name}', all L layers, {what}"}}
 
 
 def main():
@@ -78,7 +106,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=3, help="workload index 0..4 (default 3)")
+    ap.add_argument("--config", type=int, default=None,
+                    help="workload index 0..4; default: 4 (headline) and 3, both target configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--force-int64", action="store_true", help="time the general integer kernels")
     ap.add_argument("--no-u32", action="store_true", help="keep 64-bit keys (GALV_DP_NO_U32)")
@@ -147,22 +176,12 @@ def main():
         print(json.dumps(out))
         return
 
-    w = workloads.config(args.config)
-    base_flags = ((binding.GALV_DP_FORCE_INT64 if args.force_int64 else 0) |
-                  (binding.GALV_DP_NO_U32 if args.no_u32 else 0) |
-                  (binding.GALV_DP_BP_U8 if args.bp_u8 else 0))
-    dev = binding.upload(w)
-    torch.cuda.synchronize()
-
-    if args.calibrate_copy:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
+    configs = [args.config] if args.config is not None else [4, 3]
     if args.coarsen:
+        cfg = configs[-1]
+        w = workloads.config(cfg)
+        dev = binding.upload(w)
+        torch.cuda.synchronize()
         fuse, gran = (int(x) for x in args.coarsen.split(","))
         fine = binding.Solver(w.B, w.L, w.S, w.E_max, w.nR)
         fine.solve(*dev)
@@ -190,7 +209,7 @@ def main():
         both = (fine_cost < binding.GALV_INF) & (cost < binding.GALV_INF)
         rel = (cost[both] - fine_cost[both]) / fine_cost[both]
         print(json.dumps({
-            "metric": "coarsened_search", "config": {"workload": f"config {args.config} '{w.name}'",
+            "metric": "coarsened_search", "config": {"workload": f"config {cfg} '{w.name}'",
                                                       "fuse": fuse, "granularity": gran},
             "ms_per_step": ms, "searches_per_sec": w.B / (ms * 1e-3),
             "layers": [w.L, Lc], "budget_columns": [w.E_max + 1, w.E_max // gran + 1],
@@ -199,6 +218,31 @@ def main():
             "cost_error_mean": float(rel.mean()) if rel.size else None,
             "cost_error_max": float(rel.max()) if rel.size else None}))
         return
+
+
+    records = {cfg: run_config(cfg, args, torch, binding, workloads) for cfg in configs}
+    out = dict(records[configs[0]])           # the headline: the first configuration timed
+    if len(configs) > 1:
+        out["per_config"] = {str(cfg): rec for cfg, rec in records.items()}
+    print(json.dumps(out))
+
+
+def run_config(cfg, args, torch, binding, workloads):
+    """Time one named configuration; returns its record (the JSON line's fields)."""
+    w = workloads.config(cfg)
+    base_flags = ((binding.GALV_DP_FORCE_INT64 if args.force_int64 else 0) |
+                  (binding.GALV_DP_NO_U32 if args.no_u32 else 0) |
+                  (binding.GALV_DP_BP_U8 if args.bp_u8 else 0))
+    dev = binding.upload(w)
+    torch.cuda.synchronize()
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     def timed(flags, steps, warmup):
         """K steps (solve + backtrack) on a fresh handle: wall ms per step, solve ms per step."""
@@ -281,12 +325,13 @@ def main():
     binding_obj = alu_obj if bound == "alu" else hbm_obj
     roofline = {"bound": bound, "kernel": "sweep_kernel", "achieved": binding_obj["achieved"],
                 "peak": binding_obj["peak"], "unit": binding_obj["unit"], "frac": binding_obj["frac"],
-                "traffic": None if (args.force_int64 or args.bp_u8) else MEASURED_TRAFFIC_BYTES.get(args.config),
+                "traffic": None if (args.force_int64 or args.bp_u8) else MEASURED_TRAFFIC_BYTES.get(cfg),
                 "launch_ms": sweep_ms,
                 "time_at_peak_us": {"alu": t_alu * 1e6, "hbm": t_hbm * 1e6},
-                "note": "per layer step of the whole batch; with internal streams a layer step is "
-                        "several overlapping launches, so single_stream gives the one-launch-per-layer "
-                        "figure that a kernel trace shows directly (ALU fraction)",
+                "note": "per layer step of the whole batch, from events on the caller's stream around the "
+                        "solve; with internal streams a layer step is several overlapping launches, so this "
+                        "figure rests on event timing only; single_stream is the kernel's own figure (one "
+                        "launch per layer, the duration a kernel trace of --streams 1 shows; ALU fraction)",
                 "single_stream": single, "alu": alu_obj, "hbm": hbm_obj}
 
     kinds = {3: "u32", 0: "f64", 2: "f64", 1: "int64"}
@@ -302,7 +347,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dtype,
         "data": "synthetic",
-        "config": {"workload": f"config {args.config} '{w.name}': B={w.B} L={w.L} S={w.S} "
+        "config": {"workload": f"config {cfg} '{w.name}': B={w.B} L={w.L} S={w.S} "
                                f"E_max={w.E_max} budgets {int(w.budget.min())}..{int(w.budget.max())}",
                    "back_pointer_bytes": 1 if args.bp_u8 else 4,
                    "internal_streams": "auto" if args.streams == 0 else args.streams,
@@ -327,7 +372,9 @@ def main():
         out["variant_bp_u8"] = {"ms_per_step": ms_u8, "value": nominal / (ms_u8 * 1e-3)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
-    print(json.dumps(out))
+    del dev
+    torch.cuda.empty_cache()
+    return out
 
 
 if __name__ == "__main__":

@@ -117,7 +117,8 @@ struct Layout {
     int32_t b_off, b_step; // a sweep launch covers instances b_off + z * b_step (dealt over streams)
     double *Rk;           // R * 2^k + s'        [B][nR][S][S_pad] (+inf in padded columns)
     uint64_t *ck;         // per-mode c(l,s)     [B][L][S_pad]
-    uint64_t *vlist;      // usable strategies of each layer, ascending: shift << 32 | s'  [B][L][S]
+    uint64_t *vlist;      // usable strategies of each layer, ascending: shift << 32 | s'; the last one repeats
+                          // up to the row's end  [B][L][S_pad]
     int32_t *nvalid;      // how many of them    [B][L]
     uint32_t *dclamp;     // 32-bit-key path: largest R + 1, the clamp of relative costs  [B]
     int32_t *status;      // per instance        [B]
@@ -370,13 +371,17 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
     // order, with their shift: the sweep of the next layer walks this list instead
     // of all S columns (a column that never fits is infinity everywhere).
     for (int64_t l = tid; l < L; l += kThreads) {
-        uint64_t *lst = a.vlist + ((int64_t)b * L + l) * S;
+        uint64_t *lst = a.vlist + ((int64_t)b * L + l) * a.S_pad;
         int n = 0;
         for (int s = 0; s < (int)S; ++s) {
             const int sh = m[l * S + s];
             if (sh <= budget) lst[n++] = ((uint64_t)(uint32_t)sh << 32) | (uint32_t)s;
         }
         a.nvalid[(int64_t)b * L + l] = n;
+        // Past the list's end its last entry repeats (it changes no minimum: min(x, x) = x), so
+        // a sweep that walks a fixed number of entries needs no bound check; an empty list is
+        // never walked.
+        for (int i = n; i < a.S_pad && n > 0; ++i) lst[i] = lst[n - 1];
     }
 }
 
@@ -550,19 +555,16 @@ __device__ __forceinline__ void rgroup_await(RGroup<2> &g) {
 // Fast body.  Lane owns TE budget columns (64 apart) and TS strategy columns; per
 // usable s' it loads its TE shifted previous-layer cells once and reuses them for
 // all TS strategies, with the R keys as wave-uniform scalars.
-template <int TS, int TE, int NG, class Store, class BP>
-__device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int budget,
-                                           int64_t tile_start) {
+// The wave's position is explicit: its first budget column e_wave and its first strategy s0.
+template <int TS, int TE, class Store, class BP>
+__device__ __forceinline__ void sweep_fast_at(const Layout &a, int l, int b, int budget,
+                                              int64_t e_wave, int64_t s0) {
     using Cell = typename Store::Cell;
     constexpr int64_t kPerSlot = 8 / sizeof(Cell);     // cells per reserved 8-byte slot
-    const int wave = uniform(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
-    const int g = wave % NG;                       // strategy group of this wave
-    const int esub = wave / NG;                    // budget sub-tile of this wave
-    const int64_t e0 = tile_start + (int64_t)esub * (kWave * TE) + lane;
-    const int64_t s0 = ((int64_t)blockIdx.y * NG + g) * TS;
+    const int64_t e0 = e_wave + lane;
     if (s0 >= a.S) return;
-    if (tile_start + (int64_t)esub * (kWave * TE) > budget) return;
+    if (e_wave > budget) return;
 
     const int64_t S = a.S;
     const int k = a.k_bits;
@@ -593,7 +595,7 @@ __device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int bu
     //  * the R keys of a row arrive in groups of up to 16 doubles through explicit
     //    scalar loads into one of two SGPR buffers: the next group is requested
     //    before the current one is consumed and awaited after it.
-    const ConstPtr<uint64_t> vl = as_const(a.vlist + ((int64_t)b * a.L + (l - 1)) * S);
+    const ConstPtr<uint64_t> vl = as_const(a.vlist + ((int64_t)b * a.L + (l - 1)) * a.S_pad);
     const int n = as_const(a.nvalid)[(int64_t)b * a.L + (l - 1)];
     if (n > 0) {
         constexpr int kChunks = TS > 8 ? 2 : 1;            // scalar loads per group
@@ -669,6 +671,17 @@ __device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int bu
     }
 }
 
+// Position of a wave in a workgroup of NG strategy groups x (waves / NG) budget sub-tiles.
+template <int TS, int TE, int NG, class Store, class BP>
+__device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int budget,
+                                           int64_t tile_start) {
+    const int wave = uniform(threadIdx.x >> 6);
+    const int g = wave % NG;                       // strategy group of this wave
+    const int esub = wave / NG;                    // budget sub-tile of this wave
+    sweep_fast_at<TS, TE, Store, BP>(a, l, b, budget, tile_start + (int64_t)esub * (kWave * TE),
+                                     ((int64_t)blockIdx.y * NG + g) * TS);
+}
+
 // ------------------------------------------------------- 32-bit integer keys
 //
 // When costs fit 32 bits and twice the largest transition cost R_max still leaves
@@ -686,6 +699,7 @@ __device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int bu
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 typedef uint32_t uint8v __attribute__((ext_vector_type(8)));
 typedef uint32_t uint16v __attribute__((ext_vector_type(16)));
+typedef uint16v uint16v_u __attribute__((aligned(8)));      // 16 words at any 8-byte boundary
 
 // The R keys of one former strategy for TS strategy columns, in as few scalar registers as
 // the loads allow (8, 8 + 4 or 16): four such rows are live at a time.
@@ -802,7 +816,7 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int bud
     const ConstPtr<uint32_t> Rk =
         as_const(reinterpret_cast<const uint32_t *>(a.Rk + ((int64_t)b * a.nR + r) * S * a.S_pad) + s0);
     const ConstPtr<uint64_t> ck = as_const(a.ck + ((int64_t)b * a.L + l) * a.S_pad + s0);
-    const ConstPtr<uint64_t> vl = as_const(a.vlist + ((int64_t)b * a.L + (l - 1)) * S);
+    const ConstPtr<uint64_t> vl = as_const(a.vlist + ((int64_t)b * a.L + (l - 1)) * a.S_pad);
     const int n = as_const(a.nvalid)[(int64_t)b * a.L + (l - 1)];
     const uint32_t dmax = as_const(a.dclamp)[b];
 
@@ -994,6 +1008,135 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int bud
     }
 }
 
+// Register-resident form of the 32-bit-key body for strategy counts whose running minima AND
+// former-layer cells both fit a lane's registers (NS strategies, TE budget columns: 2 * NS * TE
+// VGPRs): a wave owns 64 * TE budget columns and ALL strategies.  The lane requests the shifted
+// cells of every usable former strategy at once (up to NS * TE loads in flight), reduces them to
+// the column minimum, turns them into keys in place, and then runs the whole minimum over s'
+// out of registers, with nothing but the scalar R loads in flight.  Every former-layer cell is
+// loaded once and converted once per wave (the tiled body converts it once per strategy group
+// and reads it twice); no LDS, no barrier.  The loop over pairs of list entries is fully
+// unrolled (registers cannot be indexed at run time) and leaves at the end of the list.
+template <int NS, int TE, class BP>
+__device__ __forceinline__ void sweep_u32_regs(const Layout &a, int l, int b, int budget,
+                                               int64_t e_wave) {
+    static_assert(NS % 2 == 0 && NS <= 64, "pairs of list entries; at most 64 loads in flight");
+    constexpr int NCH = (NS + 15) / 16;            // a row's R keys arrive in chunks of 16
+    const int lane = threadIdx.x & 63;
+    if (e_wave > budget) return;
+
+    const int64_t S = a.S;
+    const int k = a.k_bits;
+    const int64_t pitch = a.row * 2;               // 32-bit cells between the rows of two strategies
+    // wave-uniform bases; the lane adds only its own column
+    const uint32_t *Up = reinterpret_cast<const uint32_t *>(a.U[(l - 1) & 1]) +
+                         (int64_t)b * a.S_pad * pitch + a.lead + e_wave;
+    uint32_t *Un = reinterpret_cast<uint32_t *>(a.U[l & 1]) + (int64_t)b * a.S_pad * pitch + a.lead + e_wave;
+    BP *bp = static_cast<BP *>(a.bp) + ((int64_t)b * (a.L - 1) + (l - 1)) * S * a.e_pad + e_wave;
+    const int r = a.r_idx ? a.r_idx[(int64_t)b * a.L + l] : 0;
+    const ConstPtr<uint32_t> Rk =
+        as_const(reinterpret_cast<const uint32_t *>(a.Rk + ((int64_t)b * a.nR + r) * S * a.S_pad));
+    const ConstPtr<uint64_t> ck = as_const(a.ck + ((int64_t)b * a.L + l) * a.S_pad);
+    const ConstPtr<uint64_t> vl = as_const(a.vlist + ((int64_t)b * a.L + (l - 1)) * a.S_pad);
+    const int n = as_const(a.nvalid)[(int64_t)b * a.L + (l - 1)];
+    const uint32_t dmax = as_const(a.dclamp)[b];
+
+    uint32_t acc[NS][TE];
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int j = 0; j < TE; ++j) {
+            acc[s][j] = 0xffffffffu;
+            // opaque from here on: otherwise every exit of the unrolled loop below carries the
+            // constant along and gets a select per register
+            asm volatile("" : "+v"(acc[s][j]));
+        }
+    uint32_t cmin[TE];
+#pragma unroll
+    for (int j = 0; j < TE; ++j) cmin[j] = 0xffffffffu;
+
+    if (n > 0) {
+        // The list is padded with repeats of its last entry up to S_pad >= NS entries, so entry
+        // i needs no bound check.  Entries arrive eight at a time in one scalar load.
+        auto row_of = [&](int i) { return Rk + (int64_t)(uint32_t)vl[i] * a.S_pad; };
+
+        uint32_t cell[NS][TE];
+#pragma unroll
+        for (int i0 = 0; i0 < NS; i0 += 8) {
+            const uint16v_u ents = *reinterpret_cast<ConstPtr<uint16v_u>>(vl + i0);
+#pragma unroll
+            for (int i = i0; i < i0 + 8 && i < NS; ++i) {
+                const uint32_t sp = ents[2 * (i - i0)], shift = ents[2 * (i - i0) + 1];
+                const uint32_t *p = Up + (int64_t)sp * pitch - (int64_t)shift;
+#pragma unroll
+                for (int j = 0; j < TE; ++j) cell[i][j] = p[(uint32_t)lane + j * kWave];
+            }
+        }
+        // the R keys of the first pair travel while the cells arrive
+        R32Row<16> ra[2], rb[2];
+        ConstPtr<uint32_t> pa = row_of(0), pb = row_of(1);
+        ra[0].request(pa);
+        rb[0].request(pb);
+        r32_await(ra[0], rb[0]);
+#pragma unroll
+        for (int i = 0; i < NS; ++i)
+#pragma unroll
+            for (int j = 0; j < TE; ++j) cmin[j] = min(cmin[j], cell[i][j]);
+#pragma unroll
+        for (int i = 0; i < NS; ++i)
+#pragma unroll
+            for (int j = 0; j < TE; ++j) cell[i][j] = min(cell[i][j] - cmin[j], dmax) << k;
+
+#pragma unroll
+        for (int pr = 0; pr < NS / 2; ++pr) {
+            if (2 * pr < n) {
+                ConstPtr<uint32_t> pa_next = pa, pb_next = pb;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) {
+                    const int cur = (pr * NCH + c) & 1, nxt = cur ^ 1;
+                    // the keys of the next step (this pair's next chunk, or the next pair's first
+                    // chunk) travel under this step's arithmetic
+                    if (c + 1 < NCH) {
+                        ra[nxt].request(pa + 16 * (c + 1));
+                        rb[nxt].request(pb + 16 * (c + 1));
+                    } else {
+                        pa_next = row_of(2 * pr + 2);
+                        pb_next = row_of(2 * pr + 3);
+                        ra[nxt].request(pa_next);
+                        rb[nxt].request(pb_next);
+                    }
+#pragma unroll
+                    for (int x = 0; x < 16; ++x)
+                        if (16 * c + x < NS)
+                            minplus_u32x2<TE>(acc[16 * c + x], cell[2 * pr], cell[2 * pr + 1],
+                                              ra[cur].at(x), rb[cur].at(x), ra[nxt], rb[nxt]);
+                    r32_await(ra[nxt], rb[nxt]);
+                }
+                pa = pa_next;
+                pb = pb_next;
+            }
+        }
+    }
+
+    const uint32_t mask = (1u << k) - 1u;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        if (s < S) {
+            const uint32_t cs = (uint32_t)ck[s];
+            uint32_t *un = Un + (int64_t)s * pitch;
+            BP *bs = bp + (int64_t)s * a.e_pad;
+#pragma unroll
+            for (int j = 0; j < TE; ++j) {
+                const bool alive = cmin[j] < kInf32;
+                const uint32_t key = acc[s][j];
+                un[(uint32_t)lane + j * kWave] = alive ? cmin[j] + (key >> k) + cs : kInf32;
+                __builtin_nontemporal_store((BP)(alive ? (int32_t)(key & mask) : -1),
+                                            &bs[(uint32_t)lane + j * kWave]);
+            }
+        }
+    }
+}
+
 // UX: the 32-bit-key body keeps half-size accumulators, so it may take UX (1 or 2) times
 // the budget columns per lane; the 64-bit-key bodies then cover the same tile in UX steps.
 template <int TS, int TE, int NG, int WPE, class BP, int W, int UX, int STAGE>
@@ -1004,7 +1147,19 @@ __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) 
     const int budget = a.budget[b];
     const int64_t tile_start = (int64_t)blockIdx.x * a.tile_e;
     if (tile_start > budget) return;
-    if (st == GALV_INSTANCE_OK_FAST_U32) {
+    if constexpr (STAGE == 3) {
+        // a wave owns 64 * TE columns and all strategies (TS >= S, one strategy group)
+        const int64_t e_wave = tile_start + (int64_t)uniform(threadIdx.x >> 6) * (kWave * TE);
+        if (st == GALV_INSTANCE_OK_FAST_U32) {
+            sweep_u32_regs<TS, TE, BP>(a, l, b, budget, e_wave);
+        } else if (st == GALV_INSTANCE_OK_FAST) {
+            for (int s0 = 0; s0 < a.S; s0 += 11) sweep_fast_at<11, TE, Narrow, BP>(a, l, b, budget, e_wave, s0);
+        } else if (st == GALV_INSTANCE_OK_FAST_WIDE) {
+            for (int s0 = 0; s0 < a.S; s0 += 11) sweep_fast_at<11, TE, Wide, BP>(a, l, b, budget, e_wave, s0);
+        } else {
+            if (blockIdx.y == 0) sweep_int64<8>(a, l, b, budget, tile_start);
+        }
+    } else if (st == GALV_INSTANCE_OK_FAST_U32) {
         sweep_u32<TS, TE * UX, NG, BP, STAGE>(a, l, b, budget, tile_start);
     } else if (st == GALV_INSTANCE_OK_FAST) {
         for (int h = 0; h < UX; ++h)
@@ -1409,7 +1564,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     a.k_bits = k;
     a.tile_e = kWave * v.te * v.ux * (v.w / v.ng);
     // staged cells [sub-tile][S][columns], then (mode 2) partial column minima [wave][columns]
-    p->lds_bytes = v.stage ? (unsigned)(((size_t)(v.w / v.ng) * a.S + (v.stage == 2 ? v.w : 0)) * kWave *
+    p->lds_bytes = (v.stage == 1 || v.stage == 2) ? (unsigned)(((size_t)(v.w / v.ng) * a.S + (v.stage == 2 ? v.w : 0)) * kWave *
                                         v.te * v.ux * sizeof(uint32_t))
                            : 0u;
     if (p->lds_bytes > 160u * 1024u)
@@ -1439,7 +1594,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     // + slack: a group of R keys is fetched whole even when it straddles the row end
     p->off_Rk = take((size_t)a.B * a.nR * a.S * a.S_pad * sizeof(double) + 1024);
     p->off_ck = take((size_t)a.B * a.L * a.S_pad * sizeof(uint64_t));
-    p->off_vlist = take((size_t)a.B * a.L * a.S * sizeof(uint64_t));
+    p->off_vlist = take((size_t)a.B * a.L * a.S_pad * sizeof(uint64_t) + 64);   // + slack: entries are fetched eight at a time
     p->off_nvalid = take((size_t)a.B * a.L * sizeof(int32_t));
     p->off_status = take((size_t)a.B * sizeof(int32_t));
     p->off_last = take((size_t)a.B * sizeof(int32_t));

@@ -7,7 +7,7 @@ import torch
 
 import oracle
 from paper_2211_13878_amd import binding, workloads
-from test_gpu_parity import check_against_oracle, check_properties
+from test_gpu_parity import check_against_oracle, check_properties, config4_small_budget
 
 pytestmark = pytest.mark.gpu
 INF = binding.GALV_INF
@@ -32,16 +32,16 @@ def test_named_configs_with_tables():
 
 def test_config3_full_size_sampled_instances():
     w = workloads.config(3)
-    cost, last, plan, _ = check_against_oracle(w, flags=U8, threads=8, oracle_instances=[0, 2, 9, 30, 63])
+    ids = [0, 2, 9, 30, 31, 63]                 # 30 is the one instance without any plan
+    cost, last, plan, _ = check_against_oracle(w, flags=U8, threads=8, oracle_instances=ids,
+                                               table_instances=[31], clast_instances=ids)
     check_properties(w, cost, last, plan)
 
 
 def test_config4_shape_small_budget_full_tables():
-    w = workloads.config(4, 2)
-    w.budget[:] = [1500, 2600]
-    w.E_max = 2600
+    w, refs = config4_small_budget()
     for flags in (U8, U8 | binding.GALV_DP_FORCE_INT64):
-        check_against_oracle(w, flags=flags, table_instances=[0, 1])
+        check_against_oracle(w, flags=flags, table_instances=[0, 1], refs=refs)
 
 
 @pytest.mark.parametrize("S", [1, 9, 23, 44, 64, 130, 255])

@@ -1,6 +1,8 @@
 """GPU parity: the HIP library (through its C ABI) against the CPU oracle, bit
 for bit, on the same seeded inputs.  Costs are int64, plans and back-pointers
 int32; every comparison is exact equality."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -15,16 +17,20 @@ assert INF == oracle.INF
 # the three arithmetic paths a small-valued instance can be sent down: 32-bit integer keys
 # (default), 64-bit keys in 32-bit cells, general 64-bit integers
 ALL_PATHS = (0, binding.GALV_DP_NO_U32, binding.GALV_DP_FORCE_INT64)
+THREADS = max(1, min(16, os.cpu_count() or 1))      # oracle instances solved side by side
 
 
-def gpu_solve(w, flags=0, tables=(), want_bp=True):
-    """Run the library on a workload; returns numpy results and exported tables."""
+def gpu_solve(w, flags=0, tables=(), want_bp=True, clast=()):
+    """Run the library on a workload; returns numpy results and exported tables
+    (`tables`: C_last and, with want_bp, back-pointers; `clast`: C_last only)."""
     sol = binding.Solver(w.B, w.L, w.S, w.E_max, w.nR, flags)
     dev = binding.upload(w)
     cost, last = sol.solve(*dev)
     plan = sol.backtrack()
     status = sol.status()
     exported = {}
+    for b in clast:
+        exported[b] = (sol.export_tables(b, False)[0].cpu().numpy(), None)
     for b in tables:
         C_last, bp = sol.export_tables(b, want_bp)
         exported[b] = (C_last.cpu().numpy(), None if bp is None else bp.cpu().numpy())
@@ -34,26 +40,54 @@ def gpu_solve(w, flags=0, tables=(), want_bp=True):
     return out
 
 
+def oracle_refs(w, ids, table_instances=(), clast_instances=(), threads=4):
+    """Oracle results per instance id: full tables for `table_instances`, the last layer's
+    cost table for `clast_instances`, optimum and plan for the rest."""
+    ids = list(ids)
+    tab, cl = set(table_instances), set(clast_instances) - set(table_instances)
+    refs = {}
+    plain = [b for b in ids if b not in tab and b not in cl]
+    refs.update(zip(plain, oracle.solve_workload(w, plain, threads=threads)))
+    refs.update(zip(sorted(cl), oracle.solve_workload(w, sorted(cl), threads=threads, want_C_last=True)))
+    refs.update(zip(sorted(tab), oracle.solve_workload(w, sorted(tab), threads=threads, want_C_last=True,
+                                                      want_bp=True)))
+    return refs
+
+
 def check_against_oracle(w, flags=0, table_instances=(), oracle_instances=None, threads=4,
-                         expect_status=None):
-    cost, last, plan, status, exported = gpu_solve(w, flags, table_instances)
-    ids = range(w.B) if oracle_instances is None else oracle_instances
-    refs = oracle.solve_workload(w, ids, threads=threads)
-    for b, ref in zip(ids, refs):
+                         expect_status=None, clast_instances=(), refs=None, allow_vacuous=False):
+    """Optimum, last strategy and plan of every instance (or of `oracle_instances`) against the
+    oracle; whole exported tables for `table_instances` (C_last and back-pointers) and
+    `clast_instances` (C_last).  A table comparison in which no compared cell is finite proves
+    nothing (infinity == infinity), so it fails unless the caller says that is intended."""
+    cost, last, plan, status, exported = gpu_solve(w, flags, table_instances, clast=clast_instances)
+    ids = list(range(w.B) if oracle_instances is None else oracle_instances)
+    if refs is None:
+        refs = oracle_refs(w, sorted(set(ids) | set(table_instances) | set(clast_instances)),
+                           table_instances, clast_instances, threads)
+    for b in ids:
+        ref = refs[b]
         assert int(cost[b]) == ref.best_cost, (w.name, b)
         assert int(last[b]) == ref.best_last, (w.name, b)
         assert (plan[b] == ref.plan).all(), (w.name, b)
     if expect_status is not None:
         assert (status == expect_status).all(), status
-    for b in table_instances:
-        inst = w.instance(b)
-        ref = oracle.solve(*inst, want_C_last=True, want_bp=True)
+    finite_cells = reachable_bp = 0
+    for b in sorted(set(table_instances) | set(clast_instances)):
+        ref = refs[b]
         C_last, bp = exported[b]
-        E_b = inst[4]
+        E_b = int(w.budget[b])
         assert (C_last[:E_b + 1] == ref.C_last).all(), (w.name, b)
         assert (C_last[E_b + 1:] == INF).all()
-        assert (bp[:, :E_b + 1] == ref.bp).all(), (w.name, b)
-        assert (bp[:, E_b + 1:] == -1).all()
+        finite_cells += int((ref.C_last < INF).sum())
+        if b in table_instances:
+            assert (bp[:, :E_b + 1] == ref.bp).all(), (w.name, b)
+            assert (bp[:, E_b + 1:] == -1).all()
+            reachable_bp += int((ref.bp[-1] >= 0).sum())
+    if (table_instances or clast_instances) and not allow_vacuous:
+        assert finite_cells > 0, "every compared cost cell is infinite: the comparison shows nothing"
+        if table_instances and w.L > 1:
+            assert reachable_bp > 0, "no reachable back-pointer in the last layer"
     return cost, last, plan, status
 
 
@@ -100,51 +134,157 @@ def test_config1_int64_path_prefix():
 
 
 def test_config2_full_batch():
+    """Every instance against the oracle: optimum, plan and the whole last-layer cost table;
+    all back-pointers for two of them."""
     w = workloads.config(2)
-    cost, last, plan, _ = check_against_oracle(w, table_instances=[3], threads=8,
-                                               oracle_instances=[0, 3, 7, 12, 19, 25, 30, 31])
+    cost, last, plan, _ = check_against_oracle(w, table_instances=[3, 28], clast_instances=range(w.B),
+                                               threads=THREADS,
+                                               expect_status=binding.GALV_INSTANCE_OK_FAST_U32)
     check_properties(w, cost, last, plan)
 
 
-def test_config3_full_size_sampled_instances():
-    """Whole batch on the GPU in the benchmark's launch configuration; the oracle
-    re-solves a sample of instances (smallest budgets are infeasible by design)."""
+def test_config3_full_size_every_instance():
+    """Whole batch on the GPU in the benchmark's launch configuration; the oracle re-solves
+    every instance (one of them, number 30, has no plan: its cheapest memory exceeds its
+    budget): optimum, plan and the whole last-layer cost table for all 64, every back-pointer
+    for two."""
     w = workloads.config(3)
-    cost, last, plan, _ = check_against_oracle(w, threads=8,
-                                               oracle_instances=[0, 1, 2, 9, 17, 30, 47, 63])
+    cost, last, plan, _ = check_against_oracle(w, table_instances=[21, 63], clast_instances=range(w.B),
+                                               threads=THREADS,
+                                               expect_status=binding.GALV_INSTANCE_OK_FAST_U32)
     check_properties(w, cost, last, plan)
-    assert (cost == INF).any() and (cost < INF).any()
+    assert list(np.flatnonzero(cost == INF)) == [30]
 
 
-def test_config4_full_size_properties_and_truncated_budget():
-    """Stress shape at full size.  The oracle cannot re-solve 1.4e11 candidates per
-    instance in test time, so: (i) the plan of every instance re-evaluates to its
-    reported cost and fits; (ii) because the table has at-most-e semantics, rows
-    e <= E' of the exported full-size table must equal an oracle solve at budget E';
-    (iii) the optimum is non-increasing along the budget axis."""
+# ---- configuration 4 at full size (16 x 1.4e11 candidates: two minutes of oracle per instance)
+
+def torch_checksum(t, chunk_rows=None):
+    """oracle/checksum.py's table checksum, retyped for a device tensor (int64 wraps like uint64)."""
+    flat = t.reshape(-1)
+    total = torch.zeros((), dtype=torch.int64, device=t.device)
+    step = 1 << 26
+    for lo in range(0, flat.numel(), step):
+        x = flat[lo:lo + step].to(torch.int64) + 3
+        i = torch.arange(lo, lo + x.numel(), dtype=torch.int64, device=t.device)
+        wgt = (i * -7046029254386353131 + 0x7F4A7C15) | 1          # 0x9E3779B97F4A7C15 as int64
+        total = total + (x * wgt).sum()
+    return int(total.item()) & 0xFFFFFFFFFFFFFFFF
+
+
+def read_config4_golden():
+    rows = {}
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "config4_full_budget.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            v = [int(x) for x in line.split()]
+            rows[v[0]] = dict(cost=v[1], last=v[2], n_tied=v[3], sum_C=v[4], sum_bp=v[5], plan=v[6:])
+    return rows
+
+
+@pytest.mark.timeout(900)
+def test_config4_full_size_against_stored_oracle_results_and_two_live_instances():
+    """Stress shape at full size, in the benchmark's launch configuration.
+    (i) All 16 instances against the oracle's stored full-budget results (written by
+    tests/golden/make_golden.py from oracle/ only): optimum, last strategy, plan, and the
+    checksums of the whole last-layer cost table and of the whole back-pointer table
+    (lowest-index ties: the stored tie counts are positive).
+    (ii) Two instances are re-solved by the oracle here, at the full budget, and compared cell by
+    cell: last-layer costs and every back-pointer."""
     w = workloads.config(4)
-    cost, last, plan, status, exported = gpu_solve(w, tables=[0, 11], want_bp=False)
-    check_properties(w, cost, last, plan)
+    golden = read_config4_golden()
+    assert sorted(golden) == list(range(w.B)) and all(g["n_tied"] > 0 for g in golden.values())
+    sol = binding.Solver(w.B, w.L, w.S, w.E_max, w.nR)
+    cost, last = sol.solve(*binding.upload(w))
+    plan = sol.backtrack()
+    status = sol.status().cpu().numpy()
+    cost, last, plan = cost.cpu().numpy(), last.cpu().numpy(), plan.cpu().numpy()
     assert (status == binding.GALV_INSTANCE_OK_FAST_U32).all() and (cost < INF).all()
-    E_small = 4500
-    for b in (0, 11):
-        c, m, R, r_idx, _ = w.instance(b)
-        ref = oracle.solve(c, m, R, r_idx, E_small, want_C_last=True)
-        C_last = exported[b][0]
-        assert (C_last[:E_small + 1] == ref.C_last).all()
-        assert ref.n_tied > 0
-        best = C_last.min(axis=1)
-        assert (best[1:] <= best[:-1]).all() and best[-1] == cost[b]
+    check_properties(w, cost, last, plan)
+    live = (5, 12)
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=2) as ex:      # the oracle runs while the GPU side is checked
+        futures = {b: ex.submit(oracle.solve, *w.instance(b), want_C_last=True, want_bp=True) for b in live}
+        for b in range(w.B):
+            g = golden[b]
+            assert int(cost[b]) == g["cost"] and int(last[b]) == g["last"], b
+            assert list(plan[b]) == g["plan"], b
+            C_last, bp = sol.export_tables(b, True)
+            finite = int((C_last < INF).sum())
+            assert finite > 0.8 * C_last.numel()       # nearly every budget column is reachable here
+            assert torch_checksum(C_last) == g["sum_C"], b
+            assert torch_checksum(bp) == g["sum_bp"], b
+            best = C_last.min(dim=1).values
+            assert bool((best[1:] <= best[:-1]).all()) and int(best[-1]) == cost[b]
+            if b in live:
+                ref = futures[b].result()
+                assert ref.best_cost == g["cost"] and list(ref.plan) == g["plan"] and ref.n_tied == g["n_tied"]
+                assert torch.equal(C_last.cpu(), torch.from_numpy(ref.C_last)), b
+                assert int((ref.C_last < INF).sum()) == finite
+                for l in range(w.L):                   # 34 MB of back-pointers per layer
+                    assert torch.equal(bp[l].cpu(), torch.from_numpy(ref.bp[l])), (b, l)
+                assert int((ref.bp[-1] >= 0).sum()) > 0
+                del ref
+            del C_last, bp
+    sol.close()
+
+
+def test_config4_full_size_truncated_budget_queries():
+    """At-most-e semantics at full size: rows e <= E' of the full-size table, and the plan that
+    galv_dp_backtrack_queries returns for (instance, E'), equal an oracle solve at budget E' —
+    with E' well above the instances' smallest possible memory, so that the compared cells are
+    finite."""
+    w = workloads.config(4)
+    E_small = 16384
+    ids = (3, 14)
+    sol = binding.Solver(w.B, w.L, w.S, w.E_max, w.nR)
+    sol.solve(*binding.upload(w))
+    q_inst = torch.tensor(ids, dtype=torch.int32, device="cuda")
+    q_bud = torch.full((len(ids),), E_small, dtype=torch.int32, device="cuda")
+    q_cost, q_plan = sol.backtrack_queries(q_inst, q_bud)
+    q_cost, q_plan = q_cost.cpu().numpy(), q_plan.cpu().numpy()
+    refs = oracle.solve_workload(_with_budget(w, E_small), ids, threads=2, want_C_last=True)
+    for q, (b, ref) in enumerate(zip(ids, refs)):
+        C_last = sol.export_tables(b, False)[0].cpu().numpy()
+        assert ref.best_cost < INF and int((ref.C_last < INF).sum()) > 0.25 * ref.C_last.size
+        assert (C_last[:E_small + 1] == ref.C_last).all(), b
+        assert q_cost[q] == ref.best_cost and (q_plan[q] == ref.plan).all(), b
+    sol.close()
+
+
+def _with_budget(w, budget):
+    import copy
+    w2 = copy.copy(w)
+    w2.budget = np.full_like(w.budget, budget)
+    return w2
+
+
+_CONFIG4_SMALL = {}
+
+
+def config4_small_budget():
+    """Two instances of the stress shape (S = 128, L = 128, injected ties) with budgets just
+    above their smallest possible memory (6617 and 6132 units), so that the oracle can produce
+    every cell including back-pointers in seconds and a good part of the cells is finite.
+    Returns the workload and the oracle's tables (computed once per session)."""
+    if not _CONFIG4_SMALL:
+        w = workloads.config(4, 2)
+        w.budget[:] = [8000, 9000]
+        w.E_max = 9000
+        min_mem = w.m.astype(np.int64).min(axis=2).sum(axis=1)
+        assert (min_mem < w.budget).all() and (min_mem > 6000).all()
+        _CONFIG4_SMALL["w"] = w
+        _CONFIG4_SMALL["refs"] = oracle_refs(w, [0, 1], table_instances=[0, 1], threads=2)
+        assert all(r.n_tied > 0 and r.best_cost < INF for r in _CONFIG4_SMALL["refs"].values())
+    return _CONFIG4_SMALL["w"], _CONFIG4_SMALL["refs"]
 
 
 def test_config4_shape_small_budget_full_tables():
-    """S = 128, L = 128 with injected ties, budget cut so that the oracle can check
-    every cell including back-pointers (lowest-index tie-break)."""
-    w = workloads.config(4, 2)
-    w.budget[:] = [1500, 2600]
-    w.E_max = 2600
+    """S = 128, L = 128 with injected ties: every cell including back-pointers (lowest-index
+    tie-break), on every arithmetic path."""
+    w, refs = config4_small_budget()
     for flags in ALL_PATHS:
-        check_against_oracle(w, flags=flags, table_instances=[0, 1])
+        check_against_oracle(w, flags=flags, table_instances=[0, 1], refs=refs)
 
 
 # ------------------------------------------------------- random shapes / edges
@@ -165,9 +305,10 @@ def test_random_shapes_ragged_tiles(S):
 
 
 def test_degenerate_sizes():
-    for (L, S, E) in [(1, 1, 0), (1, 7, 5), (6, 1, 9), (2, 3, 0), (3, 4, 1)]:
+    for (L, S, E) in [(1, 1, 0), (1, 7, 5), (6, 1, 15), (2, 3, 0), (3, 4, 1)]:
         w = workloads.random_workload(7, 4, L, S, E, m_range=(0, 3), c_range=(0, 5),
                                       r_range=(0, 5))
+        w.budget[0] = E                     # at least one instance at the full width
         for flags in ALL_PATHS:
             check_against_oracle(w, flags=flags, table_instances=range(4))
 
