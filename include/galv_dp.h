@@ -270,6 +270,16 @@ galv_status_t galv_dp_destroy(galv_dp_t *h);
 /* Message of the last error on this thread ("" if none). Never NULL. */
 const char *galv_dp_last_error(void);
 
+/*
+ * How this binary was built.  The layer sweep prefetches transition costs with scalar loads
+ * issued by hand, which is only safe if the compiler did not touch their destination
+ * registers while a load was in flight; the package's build step verifies that on the device
+ * assembly that goes into the library and then stamps it "isa-checked ..." (source and flag
+ * digest, compiler version).  A build made any other way says "unchecked" and must not run
+ * on a GPU; the Python binding refuses to load it.  Never NULL.
+ */
+const char *galv_dp_build_stamp(void);
+
 #ifdef __cplusplus
 }
 #endif

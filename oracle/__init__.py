@@ -8,4 +8,4 @@ this package.  The product path (the HIP library and its binding) never does.
   * ``brute_force``  — the plain definition: enumerate every plan (bruteforce.py).
 """
 from .binding import INF, OracleResult, build, solve, solve_workload  # noqa: F401
-from .bruteforce import brute_force  # noqa: F401
+from .bruteforce import brute_force, brute_force_cells  # noqa: F401

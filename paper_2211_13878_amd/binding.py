@@ -37,7 +37,7 @@ EXPORTS = ("galv_dp_workspace_bytes", "galv_dp_create", "galv_dp_solve_batched",
            "galv_dp_backtrack", "galv_dp_solve_static", "galv_dp_best_per_budget", "galv_dp_backtrack_queries",
            "galv_dp_export_tables", "galv_dp_get_status", "galv_alg1_reduce",
            "galv_dp_coarsen", "galv_dp_expand_plan",
-           "galv_dp_destroy", "galv_dp_last_error")
+           "galv_dp_destroy", "galv_dp_last_error", "galv_dp_build_stamp")
 
 
 class GalvError(RuntimeError):
@@ -64,6 +64,16 @@ def load_library() -> ctypes.CDLL:
                 f"{LIB_PATH} is missing: build it with `python -m paper_2211_13878_amd.build` "
                 "(there is no CPU fallback)")
         lib = ctypes.CDLL(LIB_PATH)
+        # Only a library that the package's build step produced may run on a GPU: that step
+        # checks the device assembly (hand-issued scalar loads, see isa_check.py) and stamps
+        # the binary; a library built any other way carries no such stamp.
+        stamp = getattr(lib, "galv_dp_build_stamp", None)
+        if stamp is not None:
+            stamp.restype = ctypes.c_char_p
+        text = stamp().decode() if stamp is not None else "no stamp"
+        if not text.startswith("isa-checked "):
+            raise ImportError(f"{LIB_PATH} was not produced by `python -m paper_2211_13878_amd.build` "
+                              f"(build stamp: {text!r}): its device code is unverified and must not run")
         vp, i32 = ctypes.c_void_p, ctypes.c_int32
         lib.galv_dp_workspace_bytes.argtypes = [ctypes.POINTER(Desc), ctypes.POINTER(ctypes.c_size_t)]
         lib.galv_dp_create.argtypes = [ctypes.POINTER(Desc), vp, ctypes.c_size_t, ctypes.POINTER(vp)]
@@ -78,7 +88,7 @@ def load_library() -> ctypes.CDLL:
         lib.galv_dp_coarsen.argtypes = [i32] * 6 + [vp] * 10
         lib.galv_dp_expand_plan.argtypes = [i32, i32, i32, vp, vp, vp]
         lib.galv_dp_destroy.argtypes = [vp]
-        for name in EXPORTS[:-1]:
+        for name in EXPORTS[:-2]:
             getattr(lib, name).restype = ctypes.c_int
         lib.galv_dp_last_error.restype = ctypes.c_char_p
         _lib = lib
@@ -87,6 +97,10 @@ def load_library() -> ctypes.CDLL:
 
 def galv_dp_last_error() -> str:
     return load_library().galv_dp_last_error().decode()
+
+
+def galv_dp_build_stamp() -> str:
+    return load_library().galv_dp_build_stamp().decode()
 
 
 def _check(code: int):

@@ -5,6 +5,7 @@
 from __future__ import annotations
 
 import os
+import shutil
 import subprocess
 import sys
 
@@ -33,11 +34,10 @@ def device_isa(extra_flags=()) -> str:
             return fh.read()
 
 
-def check_isa(extra_flags=()) -> int:
+def check_isa_text(text: str) -> int:
     """Verify what the hand-issued scalar loads assume about the compiler's output
     (see isa_check.py); returns the number of such loads checked, raises on a violation."""
     from .isa_check import count_requests, scalar_prefetch_violations
-    text = device_isa(extra_flags)
     bad = scalar_prefetch_violations(text)
     if bad:
         lines = "\n".join(f"  {f}: load at line {a}, line {b}: {t}" for f, a, b, t in bad[:8])
@@ -49,14 +49,41 @@ def check_isa(extra_flags=()) -> int:
     return n
 
 
-def build_library(extra_flags=(), out: str = LIB, check: bool = True) -> str:
-    """Always compiles; checks the device code; replaces the library atomically."""
-    if check:
-        check_isa(extra_flags)
-    tmp = out + f".tmp{os.getpid()}"
-    cmd = [HIPCC, *FLAGS, *extra_flags, "-o", tmp, SRC]
-    subprocess.check_call(cmd)
-    os.replace(tmp, out)
+def check_isa(extra_flags=()) -> int:
+    """The same check on a fresh device-only compile (no library is produced)."""
+    return check_isa_text(device_isa(extra_flags))
+
+
+def compiler_id() -> str:
+    """First lines of `hipcc --version`: the check's verdict holds for this compiler build only."""
+    out = subprocess.check_output([HIPCC, "--version"], text=True).split("\n")
+    return " | ".join(ln.strip() for ln in out[:2])
+
+
+def build_library(extra_flags=(), out: str = LIB) -> str:
+    """Always compiles.  The device assembly that goes INTO the library (the compiler's own
+    intermediate file, kept with --save-temps) is checked before the library is put in place,
+    so a library that exists at `out` has passed; it carries a stamp that says so, which the
+    binding asks for when it loads it.  A violation leaves `out` untouched and raises."""
+    import glob
+    import hashlib
+    import tempfile
+    with open(SRC, "rb") as fh:
+        digest = hashlib.sha256(fh.read() + " ".join([*FLAGS, *extra_flags]).encode()).hexdigest()[:16]
+    stamp = f"isa-checked src+flags {digest}; {compiler_id()}"
+    with tempfile.TemporaryDirectory() as d:
+        tmp = os.path.join(d, "libgalvdp.so")
+        cmd = [HIPCC, *FLAGS, *extra_flags, "--save-temps", f'-DGALV_DP_BUILD_STAMP="{stamp}"', "-o", tmp, SRC]
+        subprocess.check_call(cmd, cwd=d)
+        asm = glob.glob(os.path.join(d, "*gfx950*.s"))
+        if len(asm) != 1:
+            raise RuntimeError(f"expected one gfx950 assembly file among the compiler's temporaries, found {asm}")
+        with open(asm[0]) as fh:
+            n = check_isa_text(fh.read())
+        staged = out + f".tmp{os.getpid()}"
+        shutil.copyfile(tmp, staged)
+        os.chmod(staged, 0o755)
+    os.replace(staged, out)
     return out
 
 

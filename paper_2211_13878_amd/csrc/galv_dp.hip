@@ -70,6 +70,9 @@ constexpr int kMaxPp = 16;            // pipeline degrees per reduce call
 #ifndef GALV_DEPTH
 #define GALV_DEPTH 2
 #endif
+#ifndef GALV_XCD_MAP
+#define GALV_XCD_MAP 1
+#endif
 constexpr int kDepth = GALV_DEPTH;      // previous-layer loads kept in flight per wave
 constexpr int64_t kInf = GALV_INF;
 constexpr uint32_t kInf32 = 0x80000000u;             // infinity of the narrow storage
@@ -1145,7 +1148,18 @@ __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) 
     const int st = a.status[b];
     if (st < 0) return;
     const int budget = a.budget[b];
+#if GALV_XCD_MAP
+    // Workgroups go round-robin to the 8 XCDs in the order of their linear index, and grid.x is
+    // a multiple of 8, so blockIdx.x & 7 names the XCD.  Each XCD takes a contiguous eighth of
+    // the tiles the instance needs: neighbouring tiles read overlapping cache lines of the
+    // shifted former-layer rows, which then meet in one XCD's L2.
+    const int nt = budget / a.tile_e + 1;
+    const int per = (nt + 7) >> 3;
+    if ((int)(blockIdx.x >> 3) >= per) return;
+    const int64_t tile_start = (int64_t)((blockIdx.x & 7) * per + (blockIdx.x >> 3)) * a.tile_e;
+#else
     const int64_t tile_start = (int64_t)blockIdx.x * a.tile_e;
+#endif
     if (tile_start > budget) return;
     if constexpr (STAGE == 3) {
         // a wave owns 64 * TE columns and all strategies (TS >= S, one strategy group)
@@ -1345,12 +1359,26 @@ __global__ __launch_bounds__(kThreads) void export_kernel(Layout a, int b, int64
 // reads of S = 128 to a third of what four separate 32-strategy workgroups fetch.
 #ifndef GALV_V0
 #define GALV_V0 8, 2, 1, 8
+#endif
+#ifndef GALV_V1
 #define GALV_V1 16, 2, 1, 6
+#endif
+#ifndef GALV_V2
 #define GALV_V2 11, 2, 2, 8
+#endif
+#ifndef GALV_V3
 #define GALV_V3 16, 2, 2, 6
+#endif
+#ifndef GALV_V4
 #define GALV_V4 11, 2, 4, 8, 4, 1, 1
+#endif
+#ifndef GALV_V5
 #define GALV_V5 16, 2, 4, 6
+#endif
+#ifndef GALV_V6
 #define GALV_V6 16, 2, 8, 6, 8, 1, 2
+#endif
+#ifndef GALV_V7
 #define GALV_V7 16, 2, 8, 6, 8
 #endif
 
@@ -1604,6 +1632,9 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     return GALV_OK;
 }
 
+// grid.x of a sweep launch for n budget tiles.
+inline unsigned kGridTiles(int n) { return GALV_XCD_MAP ? (unsigned)((n + 7) / 8 * 8) : (unsigned)n; }
+
 // Point a layout's table pointers into a workspace laid out by make_plan.
 void bind_workspace(Layout &a, const Plan &p, char *ws) {
     a.U[0] = ws + p.off_U[0];
@@ -1644,7 +1675,7 @@ galv_status_t enqueue_solve(galv_dp *h, const int64_t *c_dev, const int32_t *m_d
     a.b_off = 0;
     a.b_step = 1;
     if (h->n_side <= 1 || a.L < 2) {
-        const dim3 grid(a.n_tiles, h->groups_y, a.B);
+        const dim3 grid(kGridTiles(a.n_tiles), h->groups_y, a.B);
         for (int l = 1; l < a.L; ++l) h->sweep<<<grid, h->var.w * kWave, h->lds_bytes, st>>>(a, l);
     } else {
         // Instances are independent, so their layer chains need no common barrier: each
@@ -1662,7 +1693,7 @@ galv_status_t enqueue_solve(galv_dp *h, const int64_t *c_dev, const int32_t *m_d
             Layout ag = a;
             ag.b_off = g;
             ag.b_step = h->n_side;
-            const dim3 grid(a.n_tiles, h->groups_y, count);
+            const dim3 grid(kGridTiles(a.n_tiles), h->groups_y, count);
             for (int l = 1; l < a.L; ++l) h->sweep<<<grid, h->var.w * kWave, h->lds_bytes, h->side[g]>>>(ag, l);
             err = hipEventRecord(h->join[g], h->side[g]);
             const hipError_t e2 = err == hipSuccess ? hipStreamWaitEvent(st, h->join[g], 0) : err;
@@ -1983,5 +2014,10 @@ galv_status_t galv_dp_destroy(galv_dp_t *h) {
 }
 
 const char *galv_dp_last_error(void) { return g_err; }
+
+#ifndef GALV_DP_BUILD_STAMP
+#define GALV_DP_BUILD_STAMP "unchecked"
+#endif
+const char *galv_dp_build_stamp(void) { return GALV_DP_BUILD_STAMP; }
 
 }  // extern "C"

@@ -1,4 +1,6 @@
 """The build's check on the compiler's output for the hand-issued scalar loads (CPU only)."""
+import pytest
+
 from paper_2211_13878_amd import build
 from paper_2211_13878_amd.isa_check import count_requests, scalar_prefetch_violations
 
@@ -51,3 +53,32 @@ def test_weaker_wait_does_not_count_and_control_flow_is_caught():
 def test_product_device_code_is_clean():
     """Compiles the kernels to gfx950 assembly with the library's flags and checks every request."""
     assert build.check_isa() >= 100        # every sweep variant x storage mode x back-pointer width
+
+
+def test_library_in_tree_is_stamped_and_an_unstamped_one_is_refused(tmp_path, monkeypatch):
+    """The build step stamps what it has checked; the binding loads nothing else."""
+    import subprocess
+    from paper_2211_13878_amd import binding
+    assert binding.galv_dp_build_stamp().startswith("isa-checked ")
+    assert build.compiler_id().split("|")[0].strip() in binding.galv_dp_build_stamp()
+    # a library built by hand: same symbol, no stamp from the checked build
+    src = tmp_path / "fake.c"
+    src.write_text('const char *galv_dp_build_stamp(void) { return "unchecked"; }\n')
+    lib = tmp_path / "libfake.so"
+    subprocess.check_call(["gcc", "-shared", "-fPIC", "-o", str(lib), str(src)])
+    monkeypatch.setattr(binding, "LIB_PATH", str(lib))
+    monkeypatch.setattr(binding, "_lib", None)
+    with pytest.raises(ImportError, match="unverified"):
+        binding.load_library()
+    # and one without the symbol at all
+    src.write_text("int nothing_here(void) { return 0; }\n")
+    lib = tmp_path / "libfake2.so"                      # a new name: the loader caches by path
+    subprocess.check_call(["gcc", "-shared", "-fPIC", "-o", str(lib), str(src)])
+    monkeypatch.setattr(binding, "LIB_PATH", str(lib))
+    with pytest.raises(ImportError, match="no stamp"):
+        binding.load_library()
+
+
+def test_build_has_no_way_around_the_check():
+    import inspect
+    assert "check" not in inspect.signature(build.build_library).parameters

@@ -19,7 +19,7 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle.bruteforce import brute_force, plan_cost, plan_memory
+from oracle.bruteforce import brute_force, brute_force_cells, plan_cost, plan_memory
 from paper_2211_13878_amd import workloads
 
 INF = oracle.INF
@@ -51,6 +51,42 @@ def test_config0_matches_golden_enumeration():
     # and the enumeration itself, re-run now
     cost, plan = brute_force(*w.instance(0))
     assert (cost, plan) == (gold["cost"][0], gold["plan"])
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_every_table_cell_vs_enumeration(seed):
+    """The GPU parity tests compare whole tables with the oracle's, so the oracle's cells are
+    pinned one by one: C[L-1][e][s] is the cheapest partial plan that ends in s within e units,
+    the back-pointer of (l, e, s) the lowest former strategy that attains the cell's minimum,
+    and the tie count the number of cells with several such strategies — all by enumeration of
+    partial plans.  Narrow value ranges give many ties; m = 0, unusable cells, two asymmetric
+    matrices with a non-zero diagonal."""
+    rng = np.random.default_rng(700 + seed)
+    for _ in range(6):
+        L, S = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        E = int(rng.integers(0, 11))
+        w = workloads.random_workload(int(rng.integers(1 << 30)), 1, L, S, E, nR=2, m_range=(0, 4),
+                                      c_range=(0, 3), r_range=(0, 2), infeasible=0.15,
+                                      zero_diagonal=False, budgets=[E])
+        c, m, R, r_idx, budget = w.instance(0)
+        C, bp, n_tied = brute_force_cells(c, m, R, r_idx, budget)
+        res = oracle.solve(c, m, R, r_idx, budget, want_C_last=True, want_bp=True)
+        assert res.C_last.tolist() == C[L - 1]
+        assert res.bp.tolist() == bp
+        assert res.n_tied == n_tied
+
+
+def test_tie_count_on_a_hand_made_case():
+    """Two layers, three strategies, no memory pressure: cell (1, e, s) sees the candidates
+    c(0, s') + R(s', s).  With c(0) = [5, 5, 7] and R = 0 except R[0][2] = 1, strategies 0
+    and 1 tie between s' = 0 and 1 (both 5) while strategy 2 is won by s' = 1 alone: two tied
+    cells of three per budget column."""
+    c = np.array([[5, 5, 7], [1, 1, 1]], np.int64)
+    m = np.zeros((2, 3), np.int32)
+    R = np.array([[[0, 0, 1], [0, 0, 0], [0, 0, 0]]], np.int64)
+    res = oracle.solve(c, m, R, None, 3, want_bp=True, want_C_last=True)
+    assert res.n_tied == 2 * 4                       # budget columns 0..3
+    assert res.bp[1].tolist() == [[0, 0, 1]] * 4 and res.C_last.tolist() == [[6, 6, 6]] * 4
 
 
 @pytest.mark.parametrize("seed", range(12))
