@@ -70,6 +70,9 @@ constexpr int kMaxPp = 16;            // pipeline degrees per reduce call
 #ifndef GALV_DEPTH
 #define GALV_DEPTH 2
 #endif
+#ifndef GALV_EXP_IDENTITY
+#define GALV_EXP_IDENTITY 0     // experiment only: R rows taken in list order (wrong results when a list has gaps)
+#endif
 #ifndef GALV_XCD_MAP
 #define GALV_XCD_MAP 1
 #endif
@@ -839,6 +842,12 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int bud
 
     constexpr int kCols = kWave * TE;                        // columns of one budget sub-tile
     uint32_t *mine = lds_cells + (int64_t)esub * S * kCols;   // [list entry][column]
+    // STAGE 2: behind the cells and the partial minima, per sub-tile, the number of surviving
+    // rows and the rows themselves (S + 4 words)
+    auto survivors = [&](int sub) {
+        const int64_t nsub = blockDim.x / (kWave * NG);
+        return lds_cells + nsub * S * kCols + nsub * NG * kCols + (int64_t)sub * (S + 4);
+    };
     if constexpr (STAGE) {
         // The NG waves of a sub-tile share the copying: wave g takes entries g, g + NG, ...
         if (in_budget) {
@@ -858,12 +867,23 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int bud
                             mine[(i + u * NG) * kCols + j * kWave + lane] = t[u][j];
             }
         }
+        if constexpr (STAGE == 2) {
+            if (g == 0 && lane == 0) survivors(esub)[0] = 0;
+        }
         __syncthreads();
         if constexpr (STAGE == 2) {
             // The waves that share the columns also share the work on them: each reduces a
             // part of the rows to partial column minima (kept behind the cells:
             // [sub-tile][wave][column]) and, once the minima are known, turns its part of the
             // cells into keys, so that the inner loop reads ready keys.
+            //
+            // Pruning.  A former strategy whose cost exceeds the column minimum by more than
+            // the largest transition cost (relative cost >= dmax = R_max + 1, i.e. a clamped
+            // key) can neither win nor tie a minimum of that column, whatever the strategy s:
+            // the strategy that attains the column minimum offers at most Cmin + R_max.  A row
+            // that is clamped in EVERY reachable column of the tile is therefore left out of
+            // the inner loop altogether; the waves append the rows that survive to a list (in
+            // whatever order: the minimum does not depend on it, the index rides in the key).
             uint32_t *part = lds_cells + (int64_t)(blockDim.x / (kWave * NG)) * S * kCols +
                              (int64_t)esub * NG * kCols;
             if (in_budget) {
@@ -882,12 +902,24 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int bud
                 for (int w = 0; w < NG; ++w)
 #pragma unroll
                     for (int j = 0; j < TE; ++j) cmin[j] = min(cmin[j], part[w * kCols + j * kWave + lane]);
-                for (int i = g; i < n; i += NG)
+                uint32_t *surv = survivors(esub);
+                for (int i = g; i < n; i += NG) {
+                    bool live = false;
 #pragma unroll
                     for (int j = 0; j < TE; ++j) {
                         uint32_t *c = &mine[i * kCols + j * kWave + lane];
-                        *c = min(*c - cmin[j], dmax) << k;
+                        const uint32_t d = *c - cmin[j];
+                        live |= d < dmax && cmin[j] < kInf32;
+                        *c = min(d, dmax) << k;
                     }
+                    if (__builtin_amdgcn_ballot_w64(live) != 0) {       // wave-uniform
+                        uint32_t slot = 0;
+                        if (lane == 0) slot = atomicAdd(&surv[0], 1u);
+                        slot = (uint32_t)uniform((int)slot);
+                        // the row's place in LDS and, for the R keys, its strategy index
+                        if (lane == 0) surv[1 + slot] = (uint32_t)i | ((uint32_t)vl[i] << 16);
+                    }
+                }
             }
             __syncthreads();
         }
@@ -936,18 +968,37 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int bud
             }
         }
 
-        // Pass 2: pairs of list entries.  The cells of the next pair and the R rows of the
-        // next pair are requested before the current pair is reduced.
-        const int npair = (n + 1) / 2;             // an odd tail repeats its entry: min(x, x) = x
+        // Pass 2: pairs of list entries (of surviving rows with STAGE 2).  The cells of the
+        // next pair and the R rows of the next pair are requested before the current pair is
+        // reduced.
+        const uint32_t *surv = survivors(esub);
+        const int nrow = STAGE == 2 ? uniform((int)surv[0]) : n;
+        const int npair = (nrow + 1) / 2;          // an odd tail repeats its entry: min(x, x) = x
         uint32_t va[2][TE], vb[2][TE];
         int spa[2], spb[2];
         R32Row<TS> ra[2], rb[2];
         auto request = [&](int q, int pr) {
-            const int ia = 2 * pr < n ? 2 * pr : n - 1;
-            const int ib = 2 * pr + 1 < n ? 2 * pr + 1 : n - 1;
-            const uint64_t ea = vl[ia], eb = vl[ib];
-            spa[q] = (int)(uint32_t)ea;
-            spb[q] = (int)(uint32_t)eb;
+            int ia = 2 * pr < nrow ? 2 * pr : nrow - 1;
+            int ib = 2 * pr + 1 < nrow ? 2 * pr + 1 : nrow - 1;
+            uint64_t ea = 0, eb = 0;
+            if constexpr (STAGE == 2) {
+                const uint32_t xa = (uint32_t)uniform((int)surv[1 + ia]);
+                const uint32_t xb = (uint32_t)uniform((int)surv[1 + ib]);
+                ia = (int)(xa & 0xffffu);
+                ib = (int)(xb & 0xffffu);
+                spa[q] = (int)(xa >> 16);
+                spb[q] = (int)(xb >> 16);
+            } else {
+                ea = vl[ia];
+                eb = vl[ib];
+#if GALV_EXP_IDENTITY
+                spa[q] = ia;
+                spb[q] = ib;
+#else
+                spa[q] = (int)(uint32_t)ea;
+                spb[q] = (int)(uint32_t)eb;
+#endif
+            }
             if constexpr (STAGE) {
 #pragma unroll
                 for (int j = 0; j < TE; ++j) {
@@ -979,19 +1030,21 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int bud
                 minplus_u32x2<TE>(acc[s], da, db, ra[q].at(s), rb[q].at(s), ra[q ^ 1], rb[q ^ 1]);
             r32_await(ra[q ^ 1], rb[q ^ 1]);
         };
-        request(0, 0);
-        request(1, 1);
-        ra[0].request(Rk + (int64_t)spa[0] * a.S_pad);
-        rb[0].request(Rk + (int64_t)spb[0] * a.S_pad);
-        r32_await(ra[0], rb[0]);
-        int pr = 0;
-        for (; pr + 2 <= npair; pr += 2) {
-            reduce_pair(0);
-            request(0, pr + 2);
-            reduce_pair(1);
-            request(1, pr + 3);
+        if (nrow > 0) {
+            request(0, 0);
+            request(1, 1);
+            ra[0].request(Rk + (int64_t)spa[0] * a.S_pad);
+            rb[0].request(Rk + (int64_t)spb[0] * a.S_pad);
+            r32_await(ra[0], rb[0]);
+            int pr = 0;
+            for (; pr + 2 <= npair; pr += 2) {
+                reduce_pair(0);
+                request(0, pr + 2);
+                reduce_pair(1);
+                request(1, pr + 3);
+            }
+            if (pr < npair) reduce_pair(0);
         }
-        if (pr < npair) reduce_pair(0);
     }
 
     const uint32_t mask = (1u << k) - 1u;
@@ -1061,7 +1114,11 @@ __device__ __forceinline__ void sweep_u32_regs(const Layout &a, int l, int b, in
     if (n > 0) {
         // The list is padded with repeats of its last entry up to S_pad >= NS entries, so entry
         // i needs no bound check.  Entries arrive eight at a time in one scalar load.
+#if GALV_EXP_IDENTITY
+        auto row_of = [&](int i) { return Rk + (int64_t)(i < NS ? i : NS - 1) * a.S_pad; };
+#else
         auto row_of = [&](int i) { return Rk + (int64_t)(uint32_t)vl[i] * a.S_pad; };
+#endif
 
         uint32_t cell[NS][TE];
 #pragma unroll
@@ -1595,6 +1652,8 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     p->lds_bytes = (v.stage == 1 || v.stage == 2) ? (unsigned)(((size_t)(v.w / v.ng) * a.S + (v.stage == 2 ? v.w : 0)) * kWave *
                                         v.te * v.ux * sizeof(uint32_t))
                            : 0u;
+    // mode 2 also keeps the list of surviving rows: count + S entries (+ padding) per sub-tile
+    if (v.stage == 2) p->lds_bytes += (unsigned)((size_t)(v.w / v.ng) * (a.S + 4) * sizeof(uint32_t));
     if (p->lds_bytes > 160u * 1024u)
         return fail(GALV_ERR_RANGE, "internal: staging variant needs %u bytes of LDS", p->lds_bytes);
     a.e_pad = (int64_t)round_up((size_t)a.E_max + 1, kEAlign);
