@@ -200,6 +200,16 @@ galv_status_t galv_dp_export_tables(galv_dp_t *h, int32_t instance, int64_t *C_l
 galv_status_t galv_dp_get_status(galv_dp_t *h, int32_t *status_dev, void *stream);
 
 /*
+ * Work statistics of the last solve, for instances on the 32-bit-key path (zeros otherwise):
+ *   stats_dev [B][2] int64  [b][0] former-layer rows actually reduced, [b][1] usable rows listed,
+ *                           both summed over the budget tiles and the layers 1..L-1.
+ * The sweep leaves out rows that cannot win any minimum of a tile (cost above the column minimum
+ * by more than the largest transition cost, in every column of the tile); [b][0] / [b][1] is the
+ * share of the min-plus candidates of Eq. 1 that was evaluated.  Results do not depend on it.
+ */
+galv_status_t galv_dp_get_stats(galv_dp_t *h, int64_t *stats_dev, void *stream);
+
+/*
  * Outer loop of Algorithm 1 ("Optimization Workflow" of section 3.3) over a window of
  * candidate batch sizes, on the device, from stage optima that galv_dp_solve_batched wrote.
  * For batch size ib and pipeline degree P = pp_degree[ip] the time cost is the sum of its P

@@ -35,7 +35,7 @@ GALV_INSTANCE_BAD_VALUE = -1
 
 EXPORTS = ("galv_dp_workspace_bytes", "galv_dp_create", "galv_dp_solve_batched",
            "galv_dp_backtrack", "galv_dp_solve_static", "galv_dp_best_per_budget", "galv_dp_backtrack_queries",
-           "galv_dp_export_tables", "galv_dp_get_status", "galv_alg1_reduce",
+           "galv_dp_export_tables", "galv_dp_get_status", "galv_dp_get_stats", "galv_alg1_reduce",
            "galv_dp_coarsen", "galv_dp_expand_plan",
            "galv_dp_destroy", "galv_dp_last_error", "galv_dp_build_stamp")
 
@@ -84,6 +84,7 @@ def load_library() -> ctypes.CDLL:
         lib.galv_dp_backtrack_queries.argtypes = [vp, i32, vp, vp, vp, vp, vp]
         lib.galv_dp_export_tables.argtypes = [vp, i32, vp, vp, vp]
         lib.galv_dp_get_status.argtypes = [vp, vp, vp]
+        lib.galv_dp_get_stats.argtypes = [vp, vp, vp]
         lib.galv_alg1_reduce.argtypes = [i32, i32, ctypes.POINTER(i32), vp, vp, i32, i32, vp, vp, vp]
         lib.galv_dp_coarsen.argtypes = [i32] * 6 + [vp] * 10
         lib.galv_dp_expand_plan.argtypes = [i32, i32, i32, vp, vp, vp]
@@ -188,6 +189,10 @@ def galv_dp_export_tables(h, instance, C_last, bp, stream=None):
 
 def galv_dp_get_status(h, status, stream=None):
     _check(load_library().galv_dp_get_status(h, _dev_ptr(status, torch.int32), _stream_ptr(stream)))
+
+
+def galv_dp_get_stats(h, stats, stream=None):
+    _check(load_library().galv_dp_get_stats(h, _dev_ptr(stats, torch.int64), _stream_ptr(stream)))
 
 
 # galv_alg1_state_t as six int32 words would misread the int64 fields; it is moved as raw bytes.
@@ -296,6 +301,12 @@ class Solver:
     def status(self, stream=None):
         st = torch.empty(self.B, dtype=torch.int32, device=self.device)
         galv_dp_get_status(self.handle, st, stream)
+        return st
+
+    def stats(self, stream=None):
+        """[B][2] int64: rows reduced, rows listed (32-bit-key instances; see galv_dp_get_stats)."""
+        st = torch.empty((self.B, 2), dtype=torch.int64, device=self.device)
+        galv_dp_get_stats(self.handle, st, stream)
         return st
 
     def close(self):

@@ -70,9 +70,6 @@ constexpr int kMaxPp = 16;            // pipeline degrees per reduce call
 #ifndef GALV_DEPTH
 #define GALV_DEPTH 2
 #endif
-#ifndef GALV_EXP_IDENTITY
-#define GALV_EXP_IDENTITY 0     // experiment only: R rows taken in list order (wrong results when a list has gaps)
-#endif
 #ifndef GALV_XCD_MAP
 #define GALV_XCD_MAP 1
 #endif
@@ -104,7 +101,7 @@ inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // running minima per lane, NG strategy groups per workgroup.
 struct Variant {
     int ts, te, ng, w, ux; // w: wavefronts per workgroup (w / ng budget sub-tiles); ux: see sweep_kernel
-    int stage;             // 1: the 32-bit-key body stages the former-layer cells in LDS
+    int share;             // 1: the row-sharing 32-bit-key body (one tile per workgroup, LDS for the kept rows)
 };
 
 // Everything the kernels need to find their data.  Passed by value.
@@ -130,6 +127,7 @@ struct Layout {
     int32_t *status;      // per instance        [B]
     int32_t *last;        // best last strategy  [B]
     int32_t *lead_mode;   // whose infinity leads the rows hold: 1 narrow, 2 wide, 0 none  [B]
+    unsigned long long *stats;  // 32-bit-key sweeps: rows reduced, rows listed, summed over tiles and layers  [B][2]
     const int64_t *c;
     const int32_t *m;
     const int64_t *R;
@@ -335,6 +333,8 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
         }
         status_s = st;
         a.status[b] = st;
+        a.stats[2 * b] = 0;
+        a.stats[2 * b + 1] = 0;
     }
     __syncthreads();
     const int st = status_s;
@@ -788,13 +788,15 @@ __device__ __forceinline__ void minplus_u32x2(uint32_t (&acc)[TE], const uint32_
     }
 }
 
-// STAGE: the workgroup first copies the shifted former-layer cells of its columns (all
-// usable rows) into LDS, once, and both passes read them there: HBM then sees every cell
-// once per workgroup instead of twice.  Needs S * 64 * TE * 4 bytes of LDS per budget
-// sub-tile; every wave of the workgroup reaches the one barrier.
+// Dynamic LDS of the row-sharing body below.
 extern __shared__ uint32_t lds_cells[];
 
-template <int TS, int TE, int NG, class BP, int STAGE>
+// Plain form: NG strategy groups x (waves / NG) budget sub-tiles per workgroup, every wave
+// reads the rows it needs through the caches, twice (a first pass for the column minima, a
+// second for the minimum over s'), and reduces every usable row.  It serves strategy counts
+// beyond what one workgroup of the row-sharing body covers (several strategy-group blocks along
+// grid.y).
+template <int TS, int TE, int NG, class BP>
 __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int budget,
                                           int64_t tile_start) {
     static_assert(TS <= 16, "one scalar load fetches the R keys of a row");
@@ -804,11 +806,8 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int bud
     const int esub = wave / NG;
     const int64_t e0 = tile_start + (int64_t)esub * (kWave * TE) + lane;
     const int64_t s0 = ((int64_t)blockIdx.y * NG + g) * TS;
-    const bool in_budget = tile_start + (int64_t)esub * (kWave * TE) <= budget;   // wave-uniform
-    if constexpr (!STAGE) {
-        if (s0 >= a.S) return;
-        if (!in_budget) return;
-    }
+    if (s0 >= a.S) return;
+    if (tile_start + (int64_t)esub * (kWave * TE) > budget) return;      // wave-uniform
 
     const int64_t S = a.S;
     const int k = a.k_bits;
@@ -840,101 +839,14 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int bud
         return Up + (int64_t)(uint32_t)ent * pitch - (int64_t)(ent >> 32);
     };
 
-    constexpr int kCols = kWave * TE;                        // columns of one budget sub-tile
-    uint32_t *mine = lds_cells + (int64_t)esub * S * kCols;   // [list entry][column]
-    // STAGE 2: behind the cells and the partial minima, per sub-tile, the number of surviving
-    // rows and the rows themselves (S + 4 words)
-    auto survivors = [&](int sub) {
-        const int64_t nsub = blockDim.x / (kWave * NG);
-        return lds_cells + nsub * S * kCols + nsub * NG * kCols + (int64_t)sub * (S + 4);
-    };
-    if constexpr (STAGE) {
-        // The NG waves of a sub-tile share the copying: wave g takes entries g, g + NG, ...
-        if (in_budget) {
-            for (int i = g; i < n; i += 4 * NG) {
-                uint32_t t[4][TE];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const uint32_t *p = cells(i + u * NG);
-#pragma unroll
-                    for (int j = 0; j < TE; ++j) t[u][j] = p[(uint32_t)lane + j * kWave];
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    if (i + u * NG < n)
-#pragma unroll
-                        for (int j = 0; j < TE; ++j)
-                            mine[(i + u * NG) * kCols + j * kWave + lane] = t[u][j];
-            }
-        }
-        if constexpr (STAGE == 2) {
-            if (g == 0 && lane == 0) survivors(esub)[0] = 0;
-        }
-        __syncthreads();
-        if constexpr (STAGE == 2) {
-            // The waves that share the columns also share the work on them: each reduces a
-            // part of the rows to partial column minima (kept behind the cells:
-            // [sub-tile][wave][column]) and, once the minima are known, turns its part of the
-            // cells into keys, so that the inner loop reads ready keys.
-            //
-            // Pruning.  A former strategy whose cost exceeds the column minimum by more than
-            // the largest transition cost (relative cost >= dmax = R_max + 1, i.e. a clamped
-            // key) can neither win nor tie a minimum of that column, whatever the strategy s:
-            // the strategy that attains the column minimum offers at most Cmin + R_max.  A row
-            // that is clamped in EVERY reachable column of the tile is therefore left out of
-            // the inner loop altogether; the waves append the rows that survive to a list (in
-            // whatever order: the minimum does not depend on it, the index rides in the key).
-            uint32_t *part = lds_cells + (int64_t)(blockDim.x / (kWave * NG)) * S * kCols +
-                             (int64_t)esub * NG * kCols;
-            if (in_budget) {
-                uint32_t pm[TE];
-#pragma unroll
-                for (int j = 0; j < TE; ++j) pm[j] = 0xffffffffu;
-                for (int i = g; i < n; i += NG)
-#pragma unroll
-                    for (int j = 0; j < TE; ++j) pm[j] = min(pm[j], mine[i * kCols + j * kWave + lane]);
-#pragma unroll
-                for (int j = 0; j < TE; ++j) part[g * kCols + j * kWave + lane] = pm[j];
-            }
-            __syncthreads();
-            if (in_budget) {
-#pragma unroll
-                for (int w = 0; w < NG; ++w)
-#pragma unroll
-                    for (int j = 0; j < TE; ++j) cmin[j] = min(cmin[j], part[w * kCols + j * kWave + lane]);
-                uint32_t *surv = survivors(esub);
-                for (int i = g; i < n; i += NG) {
-                    bool live = false;
-#pragma unroll
-                    for (int j = 0; j < TE; ++j) {
-                        uint32_t *c = &mine[i * kCols + j * kWave + lane];
-                        const uint32_t d = *c - cmin[j];
-                        live |= d < dmax && cmin[j] < kInf32;
-                        *c = min(d, dmax) << k;
-                    }
-                    if (__builtin_amdgcn_ballot_w64(live) != 0) {       // wave-uniform
-                        uint32_t slot = 0;
-                        if (lane == 0) slot = atomicAdd(&surv[0], 1u);
-                        slot = (uint32_t)uniform((int)slot);
-                        // the row's place in LDS and, for the R keys, its strategy index
-                        if (lane == 0) surv[1 + slot] = (uint32_t)i | ((uint32_t)vl[i] << 16);
-                    }
-                }
-            }
-            __syncthreads();
-        }
-        if (s0 >= a.S || !in_budget) return;
-    }
-
-    if (n > 0 && STAGE == 1) {
-        for (int i = 0; i < n; ++i)
-#pragma unroll
-            for (int j = 0; j < TE; ++j) cmin[j] = min(cmin[j], mine[i * kCols + j * kWave + lane]);
+    if (n > 0 && s0 == 0 && lane == 0) {           // statistics: this body reduces every listed row
+        atomicAdd(&a.stats[2 * b], (unsigned long long)n);
+        atomicAdd(&a.stats[2 * b + 1], (unsigned long long)n);
     }
     if (n > 0) {
         // Pass 1: the column minima of the former layer.  Pure loads: batches of kBatch list
         // entries, the next batch requested before the current one is reduced.
-        constexpr int kBatch = STAGE ? 1 : GALV_P1_BATCH;
+        constexpr int kBatch = GALV_P1_BATCH;
         uint32_t t[2][kBatch][TE];
         auto fetch = [&](int h, int i0) {
 #pragma unroll
@@ -950,62 +862,238 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int bud
 #pragma unroll
                 for (int j = 0; j < TE; ++j) cmin[j] = min(cmin[j], t[h][u][j]);
         };
-        if constexpr (!STAGE) {
-            fetch(0, 0);
-            int i = 0;
-            for (; i + 2 * kBatch < n; i += 2 * kBatch) {
-                fetch(1, i + kBatch);
-                fold(0);
-                fetch(0, i + 2 * kBatch);
-                fold(1);
-            }
-            if (i + kBatch < n) {
-                fetch(1, i + kBatch);
-                fold(0);
-                fold(1);
-            } else {
-                fold(0);
-            }
+        fetch(0, 0);
+        int i = 0;
+        for (; i + 2 * kBatch < n; i += 2 * kBatch) {
+            fetch(1, i + kBatch);
+            fold(0);
+            fetch(0, i + 2 * kBatch);
+            fold(1);
+        }
+        if (i + kBatch < n) {
+            fetch(1, i + kBatch);
+            fold(0);
+            fold(1);
+        } else {
+            fold(0);
         }
 
-        // Pass 2: pairs of list entries (of surviving rows with STAGE 2).  The cells of the
-        // next pair and the R rows of the next pair are requested before the current pair is
-        // reduced.
-        const uint32_t *surv = survivors(esub);
-        const int nrow = STAGE == 2 ? uniform((int)surv[0]) : n;
+        // Pass 2: pairs of list entries.  The cells of the next pair and the R rows of the
+        // next pair are requested before the current pair is reduced.
+        const int npair = (n + 1) / 2;             // an odd tail repeats its entry: min(x, x) = x
+        uint32_t va[2][TE], vb[2][TE];
+        int spa[2], spb[2];
+        R32Row<TS> ra[2], rb[2];
+        auto request = [&](int q, int pr) {
+            const int ia = 2 * pr < n ? 2 * pr : n - 1;
+            const int ib = 2 * pr + 1 < n ? 2 * pr + 1 : n - 1;
+            const uint64_t ea = vl[ia], eb = vl[ib];
+            spa[q] = (int)(uint32_t)ea;
+            spb[q] = (int)(uint32_t)eb;
+            const uint32_t *pa = Up + (int64_t)(uint32_t)ea * pitch - (int64_t)(ea >> 32);
+            const uint32_t *pb = Up + (int64_t)(uint32_t)eb * pitch - (int64_t)(eb >> 32);
+#pragma unroll
+            for (int j = 0; j < TE; ++j) {
+                va[q][j] = pa[(uint32_t)lane + j * kWave];
+                vb[q][j] = pb[(uint32_t)lane + j * kWave];
+            }
+        };
+        auto reduce_pair = [&](int q) {
+            // keys of the next pair's rows, in flight under this pair's arithmetic
+            ra[q ^ 1].request(Rk + (int64_t)spa[q ^ 1] * a.S_pad);
+            rb[q ^ 1].request(Rk + (int64_t)spb[q ^ 1] * a.S_pad);
+            uint32_t da[TE], db[TE];
+#pragma unroll
+            for (int j = 0; j < TE; ++j) {
+                da[j] = min(va[q][j] - cmin[j], dmax) << k;
+                db[j] = min(vb[q][j] - cmin[j], dmax) << k;
+            }
+#pragma unroll
+            for (int s = 0; s < TS; ++s)
+                minplus_u32x2<TE>(acc[s], da, db, ra[q].at(s), rb[q].at(s), ra[q ^ 1], rb[q ^ 1]);
+            r32_await(ra[q ^ 1], rb[q ^ 1]);
+        };
+        request(0, 0);
+        request(1, 1);
+        ra[0].request(Rk + (int64_t)spa[0] * a.S_pad);
+        rb[0].request(Rk + (int64_t)spb[0] * a.S_pad);
+        r32_await(ra[0], rb[0]);
+        int pr = 0;
+        for (; pr + 2 <= npair; pr += 2) {
+            reduce_pair(0);
+            request(0, pr + 2);
+            reduce_pair(1);
+            request(1, pr + 3);
+        }
+        if (pr < npair) reduce_pair(0);
+    }
+
+    const uint32_t mask = (1u << k) - 1u;
+#pragma unroll
+    for (int s = 0; s < TS; ++s) {
+        if (s0 + s < S) {
+            const uint32_t cs = (uint32_t)ck[s];
+#pragma unroll
+            for (int j = 0; j < TE; ++j) {
+                const bool alive = cmin[j] < kInf32;
+                const uint32_t key = acc[s][j];
+                Un[(int64_t)s * pitch + j * kWave] = alive ? cmin[j] + (key >> k) + cs : kInf32;
+                // Back-pointers are written once and read again only by the backtrack: a
+                // streaming store keeps them from pushing the cost rows, which the next
+                // layer reads back, out of the caches.  (-1 becomes 0xFF in one byte.)
+                __builtin_nontemporal_store((BP)(alive ? (int32_t)(key & mask) : -1),
+                                            &bp[(int64_t)s * a.e_pad + j * kWave]);
+            }
+        }
+    }
+}
+
+// How many surviving rows the row-sharing body below keeps in LDS for a workgroup that covers
+// `cap` strategies (host and device agree through this one function).
+constexpr int keep_rows(int cap) { return cap <= 64 ? 16 : 32; }
+
+// Row-sharing form of the 32-bit-key body, for S <= TS * NG with one budget tile of
+// 64 * TE columns per workgroup of NG waves.  Wave g owns the former-layer rows g, g + NG, ...
+// (TS of them, in registers) AND the strategy group g of the output.
+//   1. Every wave loads its rows once (shifted, coalesced) and reduces them to partial column
+//      minima; the partial minima meet in LDS (one barrier).
+//   2. With the column minimum known, a wave tests each of its rows: a row whose relative cost
+//      is clamped (>= dmax = R_max + 1) in every reachable column of the tile can neither win nor
+//      tie any minimum of the tile (the strategy that attains the column minimum offers at most
+//      Cmin + R_max) and is dropped.  The other rows are appended, as ready keys, to a short
+//      list in LDS together with their strategy index (second barrier).  The order of the list
+//      is whatever the appends make it: the minimum does not depend on it, and the lowest-index
+//      tie-break rides in the low bits of the keys.
+//   3. The inner loop runs over the surviving rows only, reading keys from LDS and R keys by
+//      scalar loads.  Should more rows survive than the list holds (transition costs that dwarf
+//      the spread of the layer costs), the workgroup falls back to the full loop over all usable
+//      rows, read again through the caches and turned into keys on the fly.
+// Only the survivors' keys live in LDS (keep_rows rows instead of S), which is what lets four
+// 8-wave workgroups share a CU at S = 128.
+template <int TS, int TE, int NG, class BP>
+__device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, int budget,
+                                                 int64_t tile_start) {
+    static_assert(TS <= 16, "one scalar load fetches the R keys of a row");
+    constexpr int kCols = kWave * TE;
+    constexpr int kKeep = keep_rows(TS * NG);
+    (void)budget;
+    const int g = uniform(threadIdx.x >> 6);       // wave = owner of rows g + NG * r = strategy group
+    const int lane = threadIdx.x & 63;
+    const int64_t e0 = tile_start + lane;
+    const int64_t s0 = (int64_t)g * TS;
+
+    const int64_t S = a.S;
+    const int k = a.k_bits;
+    const int64_t pitch = a.row * 2;               // 32-bit cells between the rows of two strategies
+    const uint32_t *Up = reinterpret_cast<const uint32_t *>(a.U[(l - 1) & 1]) +
+                         (int64_t)b * a.S_pad * pitch + a.lead + tile_start;
+    uint32_t *Un = reinterpret_cast<uint32_t *>(a.U[l & 1]) + ((int64_t)b * a.S_pad + s0) * pitch +
+                   a.lead + e0;
+    BP *bp = static_cast<BP *>(a.bp) + (((int64_t)b * (a.L - 1) + (l - 1)) * S + s0) * a.e_pad + e0;
+    const int r_sel = a.r_idx ? a.r_idx[(int64_t)b * a.L + l] : 0;
+    const ConstPtr<uint32_t> Rk =
+        as_const(reinterpret_cast<const uint32_t *>(a.Rk + ((int64_t)b * a.nR + r_sel) * S * a.S_pad) + s0);
+    const ConstPtr<uint64_t> ck = as_const(a.ck + ((int64_t)b * a.L + l) * a.S_pad + s0);
+    // the list is padded with repeats of its last entry up to S_pad = TS * NG entries
+    const ConstPtr<uint64_t> vl = as_const(a.vlist + ((int64_t)b * a.L + (l - 1)) * a.S_pad);
+    const int n = as_const(a.nvalid)[(int64_t)b * a.L + (l - 1)];
+    const uint32_t dmax = as_const(a.dclamp)[b];
+
+    uint32_t *part = lds_cells;                    // [NG][kCols] partial column minima
+    uint32_t *count = part + NG * kCols;           // surviving rows (4 words reserved)
+    uint32_t *meta = count + 4;                    // [kKeep] strategy index of a kept row
+    uint32_t *keys = meta + kKeep;                 // [kKeep][kCols] its keys
+
+    uint32_t acc[TS][TE];
+#pragma unroll
+    for (int s = 0; s < TS; ++s)
+#pragma unroll
+        for (int j = 0; j < TE; ++j) acc[s][j] = 0xffffffffu;
+    uint32_t cmin[TE];
+#pragma unroll
+    for (int j = 0; j < TE; ++j) cmin[j] = 0xffffffffu;
+
+    if (g == 0 && lane == 0) count[0] = 0;
+    uint32_t rowc[TS][TE];
+    if (n > 0) {                                   // workgroup-uniform
+        uint32_t pm[TE];
+#pragma unroll
+        for (int j = 0; j < TE; ++j) pm[j] = 0xffffffffu;
+#pragma unroll
+        for (int r = 0; r < TS; ++r) {
+            const uint64_t ent = vl[g + NG * r];
+            const uint32_t *p = Up + (int64_t)(uint32_t)ent * pitch - (int64_t)(ent >> 32);
+#pragma unroll
+            for (int j = 0; j < TE; ++j) rowc[r][j] = p[(uint32_t)lane + j * kWave];
+        }
+#pragma unroll
+        for (int r = 0; r < TS; ++r)
+#pragma unroll
+            for (int j = 0; j < TE; ++j) pm[j] = min(pm[j], rowc[r][j]);     // a repeated row changes nothing
+#pragma unroll
+        for (int j = 0; j < TE; ++j) part[g * kCols + j * kWave + lane] = pm[j];
+    }
+    __syncthreads();
+    if (n > 0) {
+#pragma unroll
+        for (int w = 0; w < NG; ++w)
+#pragma unroll
+            for (int j = 0; j < TE; ++j) cmin[j] = min(cmin[j], part[w * kCols + j * kWave + lane]);
+#pragma unroll
+        for (int r = 0; r < TS; ++r) {
+            const int i = g + NG * r;
+            if (i < n) {                           // the padding repeats a row that is listed already
+                uint32_t d[TE];
+                bool live = false;
+#pragma unroll
+                for (int j = 0; j < TE; ++j) {
+                    d[j] = rowc[r][j] - cmin[j];
+                    live |= d[j] < dmax && cmin[j] < kInf32;
+                }
+                if (__builtin_amdgcn_ballot_w64(live) != 0) {        // wave-uniform
+                    uint32_t slot = 0;
+                    if (lane == 0) slot = atomicAdd(&count[0], 1u);
+                    slot = (uint32_t)uniform((int)slot);
+                    if (slot < (uint32_t)kKeep) {
+#pragma unroll
+                        for (int j = 0; j < TE; ++j)
+                            keys[slot * kCols + j * kWave + lane] = min(d[j], dmax) << k;
+                        if (lane == 0) meta[slot] = (uint32_t)vl[i];
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (s0 >= S) return;                           // an idle strategy group has done its share of the rows
+
+    const int nsurv = n > 0 ? uniform((int)count[0]) : 0;
+    if (g == 0 && lane == 0 && n > 0) {            // statistics: how much the pruning removed
+        atomicAdd(&a.stats[2 * b], (unsigned long long)(nsurv <= kKeep ? nsurv : n));
+        atomicAdd(&a.stats[2 * b + 1], (unsigned long long)n);
+    }
+    if (nsurv > 0) {
+        const bool pruned = nsurv <= kKeep;        // workgroup-uniform
+        const int nrow = pruned ? nsurv : n;
         const int npair = (nrow + 1) / 2;          // an odd tail repeats its entry: min(x, x) = x
         uint32_t va[2][TE], vb[2][TE];
         int spa[2], spb[2];
         R32Row<TS> ra[2], rb[2];
         auto request = [&](int q, int pr) {
-            int ia = 2 * pr < nrow ? 2 * pr : nrow - 1;
-            int ib = 2 * pr + 1 < nrow ? 2 * pr + 1 : nrow - 1;
-            uint64_t ea = 0, eb = 0;
-            if constexpr (STAGE == 2) {
-                const uint32_t xa = (uint32_t)uniform((int)surv[1 + ia]);
-                const uint32_t xb = (uint32_t)uniform((int)surv[1 + ib]);
-                ia = (int)(xa & 0xffffu);
-                ib = (int)(xb & 0xffffu);
-                spa[q] = (int)(xa >> 16);
-                spb[q] = (int)(xb >> 16);
-            } else {
-                ea = vl[ia];
-                eb = vl[ib];
-#if GALV_EXP_IDENTITY
-                spa[q] = ia;
-                spb[q] = ib;
-#else
-                spa[q] = (int)(uint32_t)ea;
-                spb[q] = (int)(uint32_t)eb;
-#endif
-            }
-            if constexpr (STAGE) {
+            const int ia = 2 * pr < nrow ? 2 * pr : nrow - 1;
+            const int ib = 2 * pr + 1 < nrow ? 2 * pr + 1 : nrow - 1;
+            if (pruned) {
+                spa[q] = uniform((int)meta[ia]);
+                spb[q] = uniform((int)meta[ib]);
 #pragma unroll
                 for (int j = 0; j < TE; ++j) {
-                    va[q][j] = mine[ia * kCols + j * kWave + lane];
-                    vb[q][j] = mine[ib * kCols + j * kWave + lane];
+                    va[q][j] = keys[ia * kCols + j * kWave + lane];
+                    vb[q][j] = keys[ib * kCols + j * kWave + lane];
                 }
             } else {
+                const uint64_t ea = vl[ia], eb = vl[ib];
+                spa[q] = (int)(uint32_t)ea;
+                spb[q] = (int)(uint32_t)eb;
                 const uint32_t *pa = Up + (int64_t)(uint32_t)ea * pitch - (int64_t)(ea >> 32);
                 const uint32_t *pb = Up + (int64_t)(uint32_t)eb * pitch - (int64_t)(eb >> 32);
 #pragma unroll
@@ -1021,30 +1109,30 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int bud
             rb[q ^ 1].request(Rk + (int64_t)spb[q ^ 1] * a.S_pad);
             uint32_t da[TE], db[TE];
 #pragma unroll
-            for (int j = 0; j < TE; ++j) {
-                da[j] = STAGE == 2 ? va[q][j] : min(va[q][j] - cmin[j], dmax) << k;
-                db[j] = STAGE == 2 ? vb[q][j] : min(vb[q][j] - cmin[j], dmax) << k;
+            for (int j = 0; j < TE; ++j) {         // kept rows are keys already; others are raw cells
+                const uint32_t ka = min(va[q][j] - cmin[j], dmax) << k;
+                const uint32_t kb = min(vb[q][j] - cmin[j], dmax) << k;
+                da[j] = pruned ? va[q][j] : ka;
+                db[j] = pruned ? vb[q][j] : kb;
             }
 #pragma unroll
             for (int s = 0; s < TS; ++s)
                 minplus_u32x2<TE>(acc[s], da, db, ra[q].at(s), rb[q].at(s), ra[q ^ 1], rb[q ^ 1]);
             r32_await(ra[q ^ 1], rb[q ^ 1]);
         };
-        if (nrow > 0) {
-            request(0, 0);
-            request(1, 1);
-            ra[0].request(Rk + (int64_t)spa[0] * a.S_pad);
-            rb[0].request(Rk + (int64_t)spb[0] * a.S_pad);
-            r32_await(ra[0], rb[0]);
-            int pr = 0;
-            for (; pr + 2 <= npair; pr += 2) {
-                reduce_pair(0);
-                request(0, pr + 2);
-                reduce_pair(1);
-                request(1, pr + 3);
-            }
-            if (pr < npair) reduce_pair(0);
+        request(0, 0);
+        request(1, 1);
+        ra[0].request(Rk + (int64_t)spa[0] * a.S_pad);
+        rb[0].request(Rk + (int64_t)spb[0] * a.S_pad);
+        r32_await(ra[0], rb[0]);
+        int pr = 0;
+        for (; pr + 2 <= npair; pr += 2) {
+            reduce_pair(0);
+            request(0, pr + 2);
+            reduce_pair(1);
+            request(1, pr + 3);
         }
+        if (pr < npair) reduce_pair(0);
     }
 
     const uint32_t mask = (1u << k) - 1u;
@@ -1064,142 +1152,9 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int bud
     }
 }
 
-// Register-resident form of the 32-bit-key body for strategy counts whose running minima AND
-// former-layer cells both fit a lane's registers (NS strategies, TE budget columns: 2 * NS * TE
-// VGPRs): a wave owns 64 * TE budget columns and ALL strategies.  The lane requests the shifted
-// cells of every usable former strategy at once (up to NS * TE loads in flight), reduces them to
-// the column minimum, turns them into keys in place, and then runs the whole minimum over s'
-// out of registers, with nothing but the scalar R loads in flight.  Every former-layer cell is
-// loaded once and converted once per wave (the tiled body converts it once per strategy group
-// and reads it twice); no LDS, no barrier.  The loop over pairs of list entries is fully
-// unrolled (registers cannot be indexed at run time) and leaves at the end of the list.
-template <int NS, int TE, class BP>
-__device__ __forceinline__ void sweep_u32_regs(const Layout &a, int l, int b, int budget,
-                                               int64_t e_wave) {
-    static_assert(NS % 2 == 0 && NS <= 64, "pairs of list entries; at most 64 loads in flight");
-    constexpr int NCH = (NS + 15) / 16;            // a row's R keys arrive in chunks of 16
-    const int lane = threadIdx.x & 63;
-    if (e_wave > budget) return;
-
-    const int64_t S = a.S;
-    const int k = a.k_bits;
-    const int64_t pitch = a.row * 2;               // 32-bit cells between the rows of two strategies
-    // wave-uniform bases; the lane adds only its own column
-    const uint32_t *Up = reinterpret_cast<const uint32_t *>(a.U[(l - 1) & 1]) +
-                         (int64_t)b * a.S_pad * pitch + a.lead + e_wave;
-    uint32_t *Un = reinterpret_cast<uint32_t *>(a.U[l & 1]) + (int64_t)b * a.S_pad * pitch + a.lead + e_wave;
-    BP *bp = static_cast<BP *>(a.bp) + ((int64_t)b * (a.L - 1) + (l - 1)) * S * a.e_pad + e_wave;
-    const int r = a.r_idx ? a.r_idx[(int64_t)b * a.L + l] : 0;
-    const ConstPtr<uint32_t> Rk =
-        as_const(reinterpret_cast<const uint32_t *>(a.Rk + ((int64_t)b * a.nR + r) * S * a.S_pad));
-    const ConstPtr<uint64_t> ck = as_const(a.ck + ((int64_t)b * a.L + l) * a.S_pad);
-    const ConstPtr<uint64_t> vl = as_const(a.vlist + ((int64_t)b * a.L + (l - 1)) * a.S_pad);
-    const int n = as_const(a.nvalid)[(int64_t)b * a.L + (l - 1)];
-    const uint32_t dmax = as_const(a.dclamp)[b];
-
-    uint32_t acc[NS][TE];
-#pragma unroll
-    for (int s = 0; s < NS; ++s)
-#pragma unroll
-        for (int j = 0; j < TE; ++j) {
-            acc[s][j] = 0xffffffffu;
-            // opaque from here on: otherwise every exit of the unrolled loop below carries the
-            // constant along and gets a select per register
-            asm volatile("" : "+v"(acc[s][j]));
-        }
-    uint32_t cmin[TE];
-#pragma unroll
-    for (int j = 0; j < TE; ++j) cmin[j] = 0xffffffffu;
-
-    if (n > 0) {
-        // The list is padded with repeats of its last entry up to S_pad >= NS entries, so entry
-        // i needs no bound check.  Entries arrive eight at a time in one scalar load.
-#if GALV_EXP_IDENTITY
-        auto row_of = [&](int i) { return Rk + (int64_t)(i < NS ? i : NS - 1) * a.S_pad; };
-#else
-        auto row_of = [&](int i) { return Rk + (int64_t)(uint32_t)vl[i] * a.S_pad; };
-#endif
-
-        uint32_t cell[NS][TE];
-#pragma unroll
-        for (int i0 = 0; i0 < NS; i0 += 8) {
-            const uint16v_u ents = *reinterpret_cast<ConstPtr<uint16v_u>>(vl + i0);
-#pragma unroll
-            for (int i = i0; i < i0 + 8 && i < NS; ++i) {
-                const uint32_t sp = ents[2 * (i - i0)], shift = ents[2 * (i - i0) + 1];
-                const uint32_t *p = Up + (int64_t)sp * pitch - (int64_t)shift;
-#pragma unroll
-                for (int j = 0; j < TE; ++j) cell[i][j] = p[(uint32_t)lane + j * kWave];
-            }
-        }
-        // the R keys of the first pair travel while the cells arrive
-        R32Row<16> ra[2], rb[2];
-        ConstPtr<uint32_t> pa = row_of(0), pb = row_of(1);
-        ra[0].request(pa);
-        rb[0].request(pb);
-        r32_await(ra[0], rb[0]);
-#pragma unroll
-        for (int i = 0; i < NS; ++i)
-#pragma unroll
-            for (int j = 0; j < TE; ++j) cmin[j] = min(cmin[j], cell[i][j]);
-#pragma unroll
-        for (int i = 0; i < NS; ++i)
-#pragma unroll
-            for (int j = 0; j < TE; ++j) cell[i][j] = min(cell[i][j] - cmin[j], dmax) << k;
-
-#pragma unroll
-        for (int pr = 0; pr < NS / 2; ++pr) {
-            if (2 * pr < n) {
-                ConstPtr<uint32_t> pa_next = pa, pb_next = pb;
-#pragma unroll
-                for (int c = 0; c < NCH; ++c) {
-                    const int cur = (pr * NCH + c) & 1, nxt = cur ^ 1;
-                    // the keys of the next step (this pair's next chunk, or the next pair's first
-                    // chunk) travel under this step's arithmetic
-                    if (c + 1 < NCH) {
-                        ra[nxt].request(pa + 16 * (c + 1));
-                        rb[nxt].request(pb + 16 * (c + 1));
-                    } else {
-                        pa_next = row_of(2 * pr + 2);
-                        pb_next = row_of(2 * pr + 3);
-                        ra[nxt].request(pa_next);
-                        rb[nxt].request(pb_next);
-                    }
-#pragma unroll
-                    for (int x = 0; x < 16; ++x)
-                        if (16 * c + x < NS)
-                            minplus_u32x2<TE>(acc[16 * c + x], cell[2 * pr], cell[2 * pr + 1],
-                                              ra[cur].at(x), rb[cur].at(x), ra[nxt], rb[nxt]);
-                    r32_await(ra[nxt], rb[nxt]);
-                }
-                pa = pa_next;
-                pb = pb_next;
-            }
-        }
-    }
-
-    const uint32_t mask = (1u << k) - 1u;
-#pragma unroll
-    for (int s = 0; s < NS; ++s) {
-        if (s < S) {
-            const uint32_t cs = (uint32_t)ck[s];
-            uint32_t *un = Un + (int64_t)s * pitch;
-            BP *bs = bp + (int64_t)s * a.e_pad;
-#pragma unroll
-            for (int j = 0; j < TE; ++j) {
-                const bool alive = cmin[j] < kInf32;
-                const uint32_t key = acc[s][j];
-                un[(uint32_t)lane + j * kWave] = alive ? cmin[j] + (key >> k) + cs : kInf32;
-                __builtin_nontemporal_store((BP)(alive ? (int32_t)(key & mask) : -1),
-                                            &bs[(uint32_t)lane + j * kWave]);
-            }
-        }
-    }
-}
-
 // UX: the 32-bit-key body keeps half-size accumulators, so it may take UX (1 or 2) times
 // the budget columns per lane; the 64-bit-key bodies then cover the same tile in UX steps.
-template <int TS, int TE, int NG, int WPE, class BP, int W, int UX, int STAGE>
+template <int TS, int TE, int NG, int WPE, class BP, int W, int UX, int SHARE>
 __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) {
     const int b = a.b_off + blockIdx.z * a.b_step;
     const int st = a.status[b];
@@ -1218,20 +1173,11 @@ __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) 
     const int64_t tile_start = (int64_t)blockIdx.x * a.tile_e;
 #endif
     if (tile_start > budget) return;
-    if constexpr (STAGE == 3) {
-        // a wave owns 64 * TE columns and all strategies (TS >= S, one strategy group)
-        const int64_t e_wave = tile_start + (int64_t)uniform(threadIdx.x >> 6) * (kWave * TE);
-        if (st == GALV_INSTANCE_OK_FAST_U32) {
-            sweep_u32_regs<TS, TE, BP>(a, l, b, budget, e_wave);
-        } else if (st == GALV_INSTANCE_OK_FAST) {
-            for (int s0 = 0; s0 < a.S; s0 += 11) sweep_fast_at<11, TE, Narrow, BP>(a, l, b, budget, e_wave, s0);
-        } else if (st == GALV_INSTANCE_OK_FAST_WIDE) {
-            for (int s0 = 0; s0 < a.S; s0 += 11) sweep_fast_at<11, TE, Wide, BP>(a, l, b, budget, e_wave, s0);
-        } else {
-            if (blockIdx.y == 0) sweep_int64<8>(a, l, b, budget, tile_start);
-        }
-    } else if (st == GALV_INSTANCE_OK_FAST_U32) {
-        sweep_u32<TS, TE * UX, NG, BP, STAGE>(a, l, b, budget, tile_start);
+    if (st == GALV_INSTANCE_OK_FAST_U32) {
+        if constexpr (SHARE)
+            sweep_u32_shared<TS, TE * UX, NG, BP>(a, l, b, budget, tile_start);
+        else
+            sweep_u32<TS, TE * UX, NG, BP>(a, l, b, budget, tile_start);
     } else if (st == GALV_INSTANCE_OK_FAST) {
         for (int h = 0; h < UX; ++h)
             sweep_fast<TS, TE, NG, Narrow, BP>(a, l, b, budget, tile_start + h * (a.tile_e / UX));
@@ -1397,46 +1343,39 @@ __global__ __launch_bounds__(kThreads) void export_kernel(Layout a, int b, int64
 
 // Sweep variants, in ascending order of the strategies one workgroup covers
 // (TS * NG).  The first one that covers S is used; larger S use the last one with
-// several strategy groups along grid.y.  <TS, TE, NG, WPE[, W[, UX]]>: TS * TE running
+// several strategy groups along grid.y.  <TS, TE, NG, WPE, W, UX, SHARE>: TS * TE running
 // minima per lane (2 VGPRs each with 64-bit keys, 1 with 32-bit keys) for WPE resident
-// waves per SIMD (512 VGPRs / WPE each), W waves per workgroup (default 4), UX times
-// the columns for the 32-bit-key body (default 1), STAGE = 1 to stage the former-layer
-// cells in LDS in that body, 2 to share the column minima and the key conversion among
-// the workgroup's waves as well (only where S is bounded by the variant: the LDS need
-// is S * 64 * TE * UX * 4 bytes per budget sub-tile).  Measured: mode 1 pays for S in
-// 33..44 (3 % faster, HBM reads down from 2.1x to 1.2x the algorithmic ones; mode 2 is
-// 2 % slower there: two more barriers in a short-lived workgroup) and not for smaller
-// shapes; mode 2 pays for S = 128 (7 % faster: eight waves share the per-cell work of
-// 128 rows), where mode 1 alone does not.
-// Measured on MI355X: small register tiles at 6-8 waves per SIMD with a shallow
-// prefetch beat large tiles at 2-4 waves with a deep one (the scalar R loads and
-// the table loads are hidden by occupancy).  The last two variants' workgroups have 8
-// waves that cover 128 strategies of one tile: the waves read the same former-layer
-// cells, through LDS (S <= 128) or through the CU's cache (larger S), which cuts the HBM
-// reads of S = 128 to a third of what four separate 32-strategy workgroups fetch.
+// waves per SIMD (512 VGPRs / WPE each), W waves per workgroup, UX times the columns for
+// the 32-bit-key body, SHARE = 1 for the row-sharing 32-bit-key body (W == NG waves, each
+// owning TS rows and TS strategies of one tile of 64 * TE * UX columns; it needs
+// TS * NG >= S, so the last variant, which serves any S, uses the plain body).
+// Measured on MI355X: with the dominated rows pruned the sweep is bound by HBM, and tiles of
+// 128 columns beat 64 (longer contiguous row segments) while larger register tiles gain
+// nothing; 8 waves per SIMD do not build for TS = 16 (the compiler then spills scalar
+// registers that a hand-issued load still targets, which the build refuses).
 #ifndef GALV_V0
-#define GALV_V0 8, 2, 1, 8
+#define GALV_V0 8, 2, 1, 8, 1, 1, 1
 #endif
 #ifndef GALV_V1
-#define GALV_V1 16, 2, 1, 6
+#define GALV_V1 16, 2, 1, 6, 1, 1, 1
 #endif
 #ifndef GALV_V2
-#define GALV_V2 11, 2, 2, 8
+#define GALV_V2 11, 2, 2, 8, 2, 1, 1
 #endif
 #ifndef GALV_V3
-#define GALV_V3 16, 2, 2, 6
+#define GALV_V3 16, 2, 2, 6, 2, 1, 1
 #endif
 #ifndef GALV_V4
 #define GALV_V4 11, 2, 4, 8, 4, 1, 1
 #endif
 #ifndef GALV_V5
-#define GALV_V5 16, 2, 4, 6
+#define GALV_V5 16, 2, 4, 6, 4, 1, 1
 #endif
 #ifndef GALV_V6
-#define GALV_V6 16, 2, 8, 6, 8, 1, 2
+#define GALV_V6 16, 2, 8, 6, 8, 1, 1
 #endif
 #ifndef GALV_V7
-#define GALV_V7 16, 2, 8, 6, 8
+#define GALV_V7 16, 2, 8, 6, 8, 1, 0
 #endif
 
 // ---------------------------------------------------------------------------------------------
@@ -1556,13 +1495,15 @@ struct VariantEntry {
     Variant v;
     SweepFn fn, fn_u8;     // int32 and one-byte back-pointers
 };
-template <int TS, int TE, int NG, int WPE, int W = 4, int UX = 1, int STAGE = 0>
+template <int TS, int TE, int NG, int WPE, int W, int UX, int SHARE>
 VariantEntry variant_entry() {
-    static_assert((W == 3 || W == 4 || W == 6 || W == 8) && W % NG == 0, "strategy groups must divide the workgroup's waves");
+    static_assert((W == 1 || W == 2 || W == 3 || W == 4 || W == 6 || W == 8) && W % NG == 0,
+                  "strategy groups must divide the workgroup's waves");
+    static_assert(!SHARE || W == NG, "the row-sharing body has one budget tile per workgroup");
     static_assert((UX == 1 || UX == 2) && TE * UX <= 4, "budget columns per lane");
-    return {{TS, TE, NG, W, UX, STAGE},
-            sweep_kernel<TS, TE, NG, WPE, int32_t, W, UX, STAGE>,
-            sweep_kernel<TS, TE, NG, WPE, uint8_t, W, UX, STAGE>};
+    return {{TS, TE, NG, W, UX, SHARE},
+            sweep_kernel<TS, TE, NG, WPE, int32_t, W, UX, SHARE>,
+            sweep_kernel<TS, TE, NG, WPE, uint8_t, W, UX, SHARE>};
 }
 
 const VariantEntry &pick_variant(int S) {
@@ -1601,7 +1542,7 @@ struct Plan {
     SweepFn sweep;
     Layout lay;
     size_t off_U[2], off_bp, off_Rk, off_ck, off_vlist, off_nvalid, off_status, off_last, off_dclamp,
-        off_lead_mode, total;
+        off_lead_mode, off_stats, total;
     int groups_y;
     unsigned lds_bytes;
 };
@@ -1648,12 +1589,12 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     while ((1 << k) < a.S) ++k;
     a.k_bits = k;
     a.tile_e = kWave * v.te * v.ux * (v.w / v.ng);
-    // staged cells [sub-tile][S][columns], then (mode 2) partial column minima [wave][columns]
-    p->lds_bytes = (v.stage == 1 || v.stage == 2) ? (unsigned)(((size_t)(v.w / v.ng) * a.S + (v.stage == 2 ? v.w : 0)) * kWave *
-                                        v.te * v.ux * sizeof(uint32_t))
-                           : 0u;
-    // mode 2 also keeps the list of surviving rows: count + S entries (+ padding) per sub-tile
-    if (v.stage == 2) p->lds_bytes += (unsigned)((size_t)(v.w / v.ng) * (a.S + 4) * sizeof(uint32_t));
+    // row-sharing body: partial minima [NG][columns], count, then keep_rows rows of (strategy index, keys)
+    p->lds_bytes = 0;
+    if (v.share) {
+        const size_t cols = (size_t)kWave * v.te * v.ux, keep = keep_rows(v.ts * v.ng);
+        p->lds_bytes = (unsigned)(((size_t)v.ng * cols + 4 + keep + keep * cols) * sizeof(uint32_t));
+    }
     if (p->lds_bytes > 160u * 1024u)
         return fail(GALV_ERR_RANGE, "internal: staging variant needs %u bytes of LDS", p->lds_bytes);
     a.e_pad = (int64_t)round_up((size_t)a.E_max + 1, kEAlign);
@@ -1687,6 +1628,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     p->off_last = take((size_t)a.B * sizeof(int32_t));
     p->off_dclamp = take((size_t)a.B * sizeof(uint32_t));
     p->off_lead_mode = take((size_t)a.B * sizeof(int32_t));
+    p->off_stats = take((size_t)a.B * 2 * sizeof(unsigned long long));
     p->total = off;
     return GALV_OK;
 }
@@ -1707,6 +1649,7 @@ void bind_workspace(Layout &a, const Plan &p, char *ws) {
     a.last = reinterpret_cast<int32_t *>(ws + p.off_last);
     a.dclamp = reinterpret_cast<uint32_t *>(ws + p.off_dclamp);
     a.lead_mode = reinterpret_cast<int32_t *>(ws + p.off_lead_mode);
+    a.stats = reinterpret_cast<unsigned long long *>(ws + p.off_stats);
 }
 
 // Enqueue one whole solve (preparation, layer 0, the L-1 sweeps, final minimum) of handle h on
@@ -1990,6 +1933,15 @@ galv_status_t galv_dp_get_status(galv_dp_t *h, int32_t *status_dev, void *stream
     if (!status_dev) return fail(GALV_ERR_INVALID_ARG, "status_dev is NULL");
     if (!h->solved) return fail(GALV_ERR_STATE, "status before a successful solve");
     HIP_TRY(hipMemcpyAsync(status_dev, h->lay.status, (size_t)h->lay.B * sizeof(int32_t),
+                           hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)));
+    return GALV_OK;
+}
+
+galv_status_t galv_dp_get_stats(galv_dp_t *h, int64_t *stats_dev, void *stream) {
+    if (!h) return fail(GALV_ERR_INVALID_ARG, "handle is NULL");
+    if (!stats_dev) return fail(GALV_ERR_INVALID_ARG, "stats_dev is NULL");
+    if (!h->solved) return fail(GALV_ERR_STATE, "statistics before a successful solve");
+    HIP_TRY(hipMemcpyAsync(stats_dev, h->lay.stats, (size_t)h->lay.B * 2 * sizeof(int64_t),
                            hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)));
     return GALV_OK;
 }
