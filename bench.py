@@ -49,6 +49,9 @@ HBM_PEAK_GBS = 8000.0
 # (status code): 32-bit keys fold two candidates into two adds and one three-way minimum;
 # 64-bit keys take one add and one minimum each; the general integer path about six.
 OPS_PER_CANDIDATE = {3: 1.5, 0: 2.0, 2: 2.0, 1: 6.0}
+# lane-operations per table state that do not depend on the number of candidates, 32-bit-key path:
+# column minimum (1), relative cost and clamp test (2), new cell and back-pointer (4)
+FIXED_OPS_PER_STATE = {3: 7.0}
 # table bytes per state: cost cell read + cost cell written + int32 back-pointer written
 BYTES_PER_STATE = {3: 4 + 4 + 4, 0: 4 + 4 + 4, 2: 8 + 8 + 4, 1: 8 + 8 + 4}   # by per-instance status code
 
@@ -278,11 +281,12 @@ def run_config(cfg, args, torch, binding, workloads):
         wall = time.perf_counter() - t0
         solve_ms = sorted(a.elapsed_time(b) for a, b in ev)
         status = sol.status().cpu().numpy()
+        stats = sol.stats().cpu().numpy()
         cost = sol.best_cost.cpu().numpy()
         sol.close()
         del sol
         torch.cuda.empty_cache()
-        return wall * 1e3 / steps, solve_ms, status, cost
+        return wall * 1e3 / steps, solve_ms, status, cost, stats
 
     nominal = w.nominal_cell_updates()
     exact = w.exact_candidates()
@@ -296,12 +300,18 @@ def run_config(cfg, args, torch, binding, workloads):
         achieved = lane_ops_per_layer / (layer_ms * 1e-3) / 1e12
         return layer_ms, achieved
 
-    ms_per_step, solve_ms, status, cost = timed(base_flags | binding.GALV_DP_STREAMS(args.streams),
-                                                args.steps, args.warmup)
-    # lane-ops of one layer: per instance (E_b + 1) * S^2 candidates times its path's cost
-    lane_ops_per_layer = sum(OPS_PER_CANDIDATE.get(int(st), 0.0) * (int(e) + 1) * w.S * w.S
-                             for st, e in zip(status, w.budget))
-    ops = lane_ops_per_layer / max(1, exact / n_layer_steps)
+    ms_per_step, solve_ms, status, cost, stats = timed(base_flags | binding.GALV_DP_STREAMS(args.streams),
+                                                       args.steps, args.warmup)
+    # Share of the min-plus candidates the sweep evaluated: on the 32-bit-key path rows that cannot
+    # win any minimum of a tile are left out (the library counts rows reduced / rows listed).
+    share = [float(r) / float(n) if n > 0 else 1.0 for r, n in stats]
+    # lane-ops of one layer: per instance and table state the fixed work of its path, plus its
+    # (E_b + 1) * S^2 candidates, as far as they were evaluated, times the path's cost per candidate
+    lane_ops_per_layer = sum((FIXED_OPS_PER_STATE.get(int(st), 0.0) +
+                              f * w.S * OPS_PER_CANDIDATE.get(int(st), 0.0)) * (int(e) + 1) * w.S
+                             for st, e, f in zip(status, w.budget, share))
+    evaluated = sum(f * (int(e) + 1) * w.S * w.S for e, f in zip(w.budget, share))     # per layer
+    ops = OPS_PER_CANDIDATE.get(int(status[0]), 0.0)
     sweep_ms, achieved = alu(solve_ms)
     per_state = [BYTES_PER_STATE.get(int(st), 0) - (3 if args.bp_u8 else 0) for st in status]
     hbm_bytes = sum(p * (int(e) + 1) * w.S for p, e in zip(per_state, w.budget))   # per layer
@@ -310,13 +320,18 @@ def run_config(cfg, args, torch, binding, workloads):
     # a kernel trace shows directly (with several streams the launches overlap in time).
     single = None
     if not args.no_extra_legs:
-        _, solve_ms_1, _, _ = timed(base_flags | binding.GALV_DP_STREAMS(1), max(2, args.steps // 2), 1)
+        _, solve_ms_1, _, _, _ = timed(base_flags | binding.GALV_DP_STREAMS(1), max(2, args.steps // 2), 1)
         launch_ms_1, achieved_1 = alu(solve_ms_1)
-        single = {"achieved": achieved_1, "frac": achieved_1 / VALU_PEAK_TLANEOPS, "launch_ms": launch_ms_1}
+        single = {"launch_ms": launch_ms_1,
+                  "alu": {"achieved": achieved_1, "frac": achieved_1 / VALU_PEAK_TLANEOPS},
+                  "hbm": {"achieved": hbm_bytes / (launch_ms_1 * 1e-3) / 1e9,
+                          "frac": hbm_bytes / (launch_ms_1 * 1e-3) / 1e9 / HBM_PEAK_GBS}}
 
     # Which roofline binds: the one that needs more time at its peak for one layer's work.
     alu_obj = {"achieved": achieved, "peak": VALU_PEAK_TLANEOPS, "unit": "Tlane-op/s",
-               "frac": achieved / VALU_PEAK_TLANEOPS, "lane_ops_per_candidate": ops}
+               "frac": achieved / VALU_PEAK_TLANEOPS, "lane_ops_per_candidate": ops,
+               "lane_ops_per_state_fixed": FIXED_OPS_PER_STATE.get(int(status[0]), 0.0),
+               "candidates_evaluated_share": evaluated / max(1.0, exact / n_layer_steps)}
     hbm_obj = {"achieved": hbm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_gbs / HBM_PEAK_GBS,
                "bytes_per_launch": hbm_bytes, "bytes_per_state": max(per_state)}
     t_alu = lane_ops_per_layer / (VALU_PEAK_TLANEOPS * 1e12)
@@ -331,7 +346,9 @@ def run_config(cfg, args, torch, binding, workloads):
                 "note": "per layer step of the whole batch, from events on the caller's stream around the "
                         "solve; with internal streams a layer step is several overlapping launches, so this "
                         "figure rests on event timing only; single_stream is the kernel's own figure (one "
-                        "launch per layer, the duration a kernel trace of --streams 1 shows; ALU fraction)",
+                        "launch per layer, the duration a kernel trace of --streams 1 shows). The ALU side "
+                        "counts only the candidates the sweep evaluates (rows that cannot win any minimum "
+                        "of a tile are pruned; alu.candidates_evaluated_share, from galv_dp_get_stats)",
                 "single_stream": single, "alu": alu_obj, "hbm": hbm_obj}
 
     kinds = {3: "u32", 0: "f64", 2: "f64", 1: "int64"}
@@ -356,6 +373,7 @@ def run_config(cfg, args, torch, binding, workloads):
                    "table_states_per_batch": states},
         "searches_per_sec": w.B / (ms_per_step * 1e-3),
         "exact_candidates_per_sec": exact / (ms_per_step * 1e-3),
+        "candidates_evaluated_share": evaluated / max(1.0, exact / n_layer_steps),
         "solve_ms_median": solve_ms[len(solve_ms) // 2],
         "instances_by_path": {"u32_keys": int((status == binding.GALV_INSTANCE_OK_FAST_U32).sum()),
                               "f64_keys_32bit_cells": int((status == binding.GALV_INSTANCE_OK_FAST).sum()),
@@ -366,7 +384,7 @@ def run_config(cfg, args, torch, binding, workloads):
     }
     if not (args.bp_u8 or args.force_int64 or args.no_extra_legs) and w.S <= 255:
         # storage variant, same results: one-byte back-pointers (9 instead of 12 B per state)
-        ms_u8, _, _, cost_u8 = timed(binding.GALV_DP_BP_U8 | binding.GALV_DP_STREAMS(args.streams),
+        ms_u8, _, _, cost_u8, _ = timed(binding.GALV_DP_BP_U8 | binding.GALV_DP_STREAMS(args.streams),
                                      max(2, args.steps // 2), 1)
         assert (cost_u8 == cost).all()
         out["variant_bp_u8"] = {"ms_per_step": ms_u8, "value": nominal / (ms_u8 * 1e-3)}

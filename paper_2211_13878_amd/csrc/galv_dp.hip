@@ -117,6 +117,8 @@ struct Layout {
     char *U[2];           // rolling cost rows   [B][S_pad][row] of 8-byte slots
     void *bp;             // argmin, un-shifted  [B][L-1][S][e_pad] of int32, or of uint8 (0xFF = none)
     int32_t bp_u8;        // 1: one-byte back-pointers
+    int32_t synth_l1;     // 1: the 32-bit-key sweep makes up layer 0's cells (a constant per strategy)
+                          //    when it sweeps layer 1, so layer 0's row is never written nor read
     int32_t b_off, b_step; // a sweep launch covers instances b_off + z * b_step (dealt over streams)
     double *Rk;           // R * 2^k + s'        [B][nR][S][S_pad] (+inf in padded columns)
     uint64_t *ck;         // per-mode c(l,s)     [B][L][S_pad]
@@ -127,7 +129,7 @@ struct Layout {
     int32_t *status;      // per instance        [B]
     int32_t *last;        // best last strategy  [B]
     int32_t *lead_mode;   // whose infinity leads the rows hold: 1 narrow, 2 wide, 0 none  [B]
-    unsigned long long *stats;  // 32-bit-key sweeps: rows reduced, rows listed, summed over tiles and layers  [B][2]
+    uint32_t *stats;      // 32-bit-key sweeps: rows reduced << 16 | rows listed, per tile  [B][L-1][n_tiles]
     const int64_t *c;
     const int32_t *m;
     const int64_t *R;
@@ -333,8 +335,6 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
         }
         status_s = st;
         a.status[b] = st;
-        a.stats[2 * b] = 0;
-        a.stats[2 * b + 1] = 0;
     }
     __syncthreads();
     const int st = status_s;
@@ -421,7 +421,7 @@ __global__ __launch_bounds__(kThreads) void init_kernel(Layout a, int fresh) {
                 u0[x] = Narrow::infinity();
                 u1[x] = Narrow::infinity();
             }
-        } else {
+        } else if (!(st == GALV_INSTANCE_OK_FAST_U32 && a.synth_l1 && a.L > 1)) {
             u0[x] = Narrow::first_layer(cs);
         }
     } else {
@@ -839,10 +839,9 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int bud
         return Up + (int64_t)(uint32_t)ent * pitch - (int64_t)(ent >> 32);
     };
 
-    if (n > 0 && s0 == 0 && lane == 0) {           // statistics: this body reduces every listed row
-        atomicAdd(&a.stats[2 * b], (unsigned long long)n);
-        atomicAdd(&a.stats[2 * b + 1], (unsigned long long)n);
-    }
+    if (s0 == 0 && esub == 0 && lane == 0)         // statistics: this body reduces every listed row
+        a.stats[((int64_t)b * (a.L - 1) + (l - 1)) * a.n_tiles + (uint32_t)tile_start / (uint32_t)a.tile_e] =
+            (uint32_t)n << 16 | (uint32_t)n;
     if (n > 0) {
         // Pass 1: the column minima of the former layer.  Pure loads: batches of kBatch list
         // entries, the next batch requested before the current one is reduced.
@@ -999,6 +998,24 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
     const int n = as_const(a.nvalid)[(int64_t)b * a.L + (l - 1)];
     const uint32_t dmax = as_const(a.dclamp)[b];
 
+    // The shifted cells of one usable former strategy for this lane's columns.  Layer 0's table
+    // is a constant per strategy, U_0[e'][s'] = c(0, s'), so when layer 1 is swept its cells are
+    // made up here (infinity below the shift) instead of being read.
+    const bool first = l == 1;                     // uniform
+    const ConstPtr<uint64_t> ck0 = as_const(a.ck + (int64_t)b * a.L * a.S_pad);
+    auto load_row = [&](uint64_t ent, uint32_t (&out)[TE]) {
+        const uint32_t sp = (uint32_t)ent, shift = (uint32_t)(ent >> 32);
+        if (first) {
+            const uint32_t c0 = (uint32_t)ck0[sp];
+#pragma unroll
+            for (int j = 0; j < TE; ++j) out[j] = e0 + j * kWave >= (int64_t)shift ? c0 : kInf32;
+        } else {
+            const uint32_t *p = Up + (int64_t)sp * pitch - (int64_t)shift;
+#pragma unroll
+            for (int j = 0; j < TE; ++j) out[j] = p[(uint32_t)lane + j * kWave];
+        }
+    };
+
     uint32_t *part = lds_cells;                    // [NG][kCols] partial column minima
     uint32_t *count = part + NG * kCols;           // surviving rows (4 words reserved)
     uint32_t *meta = count + 4;                    // [kKeep] strategy index of a kept row
@@ -1020,12 +1037,7 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
 #pragma unroll
         for (int j = 0; j < TE; ++j) pm[j] = 0xffffffffu;
 #pragma unroll
-        for (int r = 0; r < TS; ++r) {
-            const uint64_t ent = vl[g + NG * r];
-            const uint32_t *p = Up + (int64_t)(uint32_t)ent * pitch - (int64_t)(ent >> 32);
-#pragma unroll
-            for (int j = 0; j < TE; ++j) rowc[r][j] = p[(uint32_t)lane + j * kWave];
-        }
+        for (int r = 0; r < TS; ++r) load_row(vl[g + NG * r], rowc[r]);
 #pragma unroll
         for (int r = 0; r < TS; ++r)
 #pragma unroll
@@ -1068,10 +1080,9 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
     if (s0 >= S) return;                           // an idle strategy group has done its share of the rows
 
     const int nsurv = n > 0 ? uniform((int)count[0]) : 0;
-    if (g == 0 && lane == 0 && n > 0) {            // statistics: how much the pruning removed
-        atomicAdd(&a.stats[2 * b], (unsigned long long)(nsurv <= kKeep ? nsurv : n));
-        atomicAdd(&a.stats[2 * b + 1], (unsigned long long)n);
-    }
+    if (g == 0 && lane == 0)                       // statistics: how much the pruning removed
+        a.stats[((int64_t)b * (a.L - 1) + (l - 1)) * a.n_tiles + (uint32_t)tile_start / (uint32_t)a.tile_e] =
+            (uint32_t)(nsurv <= kKeep ? nsurv : n) << 16 | (uint32_t)n;
     if (nsurv > 0) {
         const bool pruned = nsurv <= kKeep;        // workgroup-uniform
         const int nrow = pruned ? nsurv : n;
@@ -1094,13 +1105,8 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
                 const uint64_t ea = vl[ia], eb = vl[ib];
                 spa[q] = (int)(uint32_t)ea;
                 spb[q] = (int)(uint32_t)eb;
-                const uint32_t *pa = Up + (int64_t)(uint32_t)ea * pitch - (int64_t)(ea >> 32);
-                const uint32_t *pb = Up + (int64_t)(uint32_t)eb * pitch - (int64_t)(eb >> 32);
-#pragma unroll
-                for (int j = 0; j < TE; ++j) {
-                    va[q][j] = pa[(uint32_t)lane + j * kWave];
-                    vb[q][j] = pb[(uint32_t)lane + j * kWave];
-                }
+                load_row(ea, va[q]);
+                load_row(eb, vb[q]);
             }
         };
         auto reduce_pair = [&](int q) {
@@ -1256,6 +1262,36 @@ __device__ __forceinline__ void walk_plan(const Layout &a, int b, int64_t e, int
         }
     }
     out[0] = s;
+}
+
+// Per instance: the tiles' (rows reduced, rows listed) summed over the tiles within the budget
+// and the layers; zeros for an instance that is not on the 32-bit-key path.
+__global__ __launch_bounds__(kThreads) void stats_kernel(Layout a, int64_t *out) {
+    const int b = blockIdx.x;
+    __shared__ unsigned long long red[2][kThreads];
+    unsigned long long done = 0, listed = 0;
+    if (a.status[b] == GALV_INSTANCE_OK_FAST_U32) {
+        const int nt = a.budget[b] / a.tile_e + 1;
+        for (int64_t i = threadIdx.x; i < (int64_t)(a.L - 1) * nt; i += kThreads) {
+            const uint32_t v = a.stats[((int64_t)b * (a.L - 1) + i / nt) * a.n_tiles + i % nt];
+            done += v >> 16;
+            listed += v & 0xffffu;
+        }
+    }
+    red[0][threadIdx.x] = done;
+    red[1][threadIdx.x] = listed;
+    __syncthreads();
+    for (int w = kThreads / 2; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) {
+            red[0][threadIdx.x] += red[0][threadIdx.x + w];
+            red[1][threadIdx.x] += red[1][threadIdx.x + w];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        out[2 * b] = (int64_t)red[0][0];
+        out[2 * b + 1] = (int64_t)red[1][0];
+    }
 }
 
 // One thread per instance, from the full budget and the stored best last strategy.
@@ -1582,6 +1618,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     a.E_max = d->max_budget;
     a.nR = d->n_transition;
     a.bp_u8 = u8 ? 1 : 0;
+    a.synth_l1 = v.share ? 1 : 0;
     const int group = v.ts * v.ng;
     p->groups_y = (a.S + group - 1) / group;
     a.S_pad = p->groups_y * group;
@@ -1628,7 +1665,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     p->off_last = take((size_t)a.B * sizeof(int32_t));
     p->off_dclamp = take((size_t)a.B * sizeof(uint32_t));
     p->off_lead_mode = take((size_t)a.B * sizeof(int32_t));
-    p->off_stats = take((size_t)a.B * 2 * sizeof(unsigned long long));
+    p->off_stats = take((size_t)a.B * (a.L > 1 ? a.L - 1 : 1) * a.n_tiles * sizeof(uint32_t));
     p->total = off;
     return GALV_OK;
 }
@@ -1649,7 +1686,7 @@ void bind_workspace(Layout &a, const Plan &p, char *ws) {
     a.last = reinterpret_cast<int32_t *>(ws + p.off_last);
     a.dclamp = reinterpret_cast<uint32_t *>(ws + p.off_dclamp);
     a.lead_mode = reinterpret_cast<int32_t *>(ws + p.off_lead_mode);
-    a.stats = reinterpret_cast<unsigned long long *>(ws + p.off_stats);
+    a.stats = reinterpret_cast<uint32_t *>(ws + p.off_stats);
 }
 
 // Enqueue one whole solve (preparation, layer 0, the L-1 sweeps, final minimum) of handle h on
@@ -1789,7 +1826,7 @@ galv_status_t galv_dp_create(const galv_dp_desc_t *desc, void *workspace_dev,
         // millisecond or more run at the arithmetic limit anyway and gain 2-5 % from 2.
         const double us = 2.0 * desc->n_instances * ((double)desc->max_budget + 1) *
                           desc->n_strategies * desc->n_strategies / 2e13 * 1e6;
-        n = us < 20.0 ? 1 : (us < 150.0 ? 2 : (us < 1000.0 ? 10 : 2));
+        n = us < 20.0 ? 1 : (us < 150.0 ? 2 : (us < 1000.0 ? 9 : 2));
     }
     if (n > desc->n_instances) n = desc->n_instances;
     if (n > 1 && desc->n_layers > 1) {
@@ -1941,8 +1978,8 @@ galv_status_t galv_dp_get_stats(galv_dp_t *h, int64_t *stats_dev, void *stream) 
     if (!h) return fail(GALV_ERR_INVALID_ARG, "handle is NULL");
     if (!stats_dev) return fail(GALV_ERR_INVALID_ARG, "stats_dev is NULL");
     if (!h->solved) return fail(GALV_ERR_STATE, "statistics before a successful solve");
-    HIP_TRY(hipMemcpyAsync(stats_dev, h->lay.stats, (size_t)h->lay.B * 2 * sizeof(int64_t),
-                           hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)));
+    stats_kernel<<<h->lay.B, kThreads, 0, static_cast<hipStream_t>(stream)>>>(h->lay, stats_dev);
+    HIP_TRY(hipGetLastError());
     return GALV_OK;
 }
 
