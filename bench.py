@@ -16,16 +16,24 @@ nominal count sum_b L * E_b * S^2 per batch, in the library's default
 configuration (int32 back-pointers, internal streams chosen from the shape);
 searches/s and the exact candidate rate are reported beside it.
 
-`roofline` is for the layer-sweep kernel (the only kernel that matters: > 98 %
-of the time): exact min-plus candidates of one layer times the VALU
-lane-operations each one needs on its instance's arithmetic path (1.5 with
-32-bit keys: two adds and one three-way minimum per two candidates; 2 with
-64-bit keys: one add, one minimum), divided by the sweep time per layer (events
-on the caller's stream around the solve, / (L-1)), against the chip's VALU issue
-peak of 256 CUs x 64 lanes x 2.4 GHz = 39.3 T lane-ops/s.  With internal streams
-a layer is several overlapping launches, so that figure rests on event timing;
-`roofline.single_stream` is a second timed leg with one launch per layer, the
-kernel's own figure, which a kernel trace of `--streams 1` shows directly.
+`roofline` is for the layer-sweep kernel (the only kernel that matters: > 95 %
+of the time).  Two sides are computed per layer step, and the one that needs
+more time at its peak is the binding one (`roofline.bound`):
+  * HBM: 12 bytes per table state within the budgets (cost cell read, cost cell
+    written, int32 back-pointer written; 20 on the 64-bit-cell paths) against
+    8 TB/s;
+  * ALU: the min-plus candidates the sweep evaluates (the library counts them:
+    on the 32-bit-key path former strategies that cannot win any minimum of a
+    tile are pruned; `candidates_evaluated_share`) times the lane-operations
+    each needs on its instance's arithmetic path (1.5 with 32-bit keys: two adds
+    and one three-way minimum per two candidates; 2 with 64-bit keys), plus 7 per
+    table state on the 32-bit-key path, against the VALU issue peak of
+    256 CUs x 64 lanes x 2.4 GHz = 39.3 T lane-ops/s.
+The sweep time per layer comes from events on the caller's stream around the
+solve, / (L-1).  With internal streams a layer is several overlapping launches,
+so that figure rests on event timing; `roofline.single_stream` is a second timed
+leg with one launch per layer, the kernel's own figure, which a kernel trace of
+`--streams 1` shows directly.
 `variant_bp_u8` is a third leg with one-byte back-pointers (same results, 9
 instead of 12 B/state).
 `cpu_baseline` times the serial CPU oracle (test infrastructure, never tuned) on a
@@ -57,8 +65,9 @@ BYTES_PER_STATE = {3: 4 + 4 + 4, 0: 4 + 4 + 4, 2: 8 + 8 + 4, 1: 8 + 8 + 4}   # b
 
 
 # HBM bytes per sweep launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by the
-# same counter's reading for a 1 GiB copy (profiles/sweep_kernel_config<N>.md); None where not measured.
-MEASURED_TRAFFIC_BYTES = {3: 745100741, 4: 1771421157}
+# same counter's reading for a 1 GiB copy: the `traffic_bytes_per_launch` line of
+# profiles/sweep_kernel_config<N>.md (tests/test_profiles.py keeps the two equal); None where not measured.
+MEASURED_TRAFFIC_BYTES = {3: 685531006, 4: 1621484954}
 
 
 def cpu_baseline(w):
