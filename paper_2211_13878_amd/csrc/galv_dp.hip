@@ -393,7 +393,7 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
 
 // Layer 0: U_0[e'][s] = c(0,s) for every e' (the shift by m(0,s) is applied by
 // whoever reads it), and the infinity lead in front of both rolling rows of the
-// strategy.  Grid: (row cells / 256, S, B).
+// strategy.  Grid: (a few blocks that stride over the row, S, B).
 //
 // The leads never change while an instance keeps its storage mode, and no sweep
 // writes into them, so only the first solve of a handle (fresh != 0) and a solve
@@ -403,38 +403,36 @@ __global__ __launch_bounds__(kThreads) void init_kernel(Layout a, int fresh) {
     const int b = blockIdx.z, s = blockIdx.y;
     const int st = a.status[b];
     if (st < 0) return;
-    const int64_t x = (int64_t)blockIdx.x * kThreads + threadIdx.x;   // cell within the row
-    if (x >= a.row) return;
     const int64_t base = ((int64_t)b * a.S_pad + s) * a.row * 8;
+    const int64_t x0 = (int64_t)blockIdx.x * kThreads + threadIdx.x, step = (int64_t)gridDim.x * kThreads;
     if (st == GALV_INSTANCE_OK_INT64) {
-        if (x >= a.lead)
-            reinterpret_cast<int64_t *>(a.U[0] + base)[x] = a.c[((int64_t)b * a.L) * a.S + s];
+        const int64_t c0 = a.c[((int64_t)b * a.L) * a.S + s];
+        for (int64_t x = a.lead + x0; x < a.row; x += step) reinterpret_cast<int64_t *>(a.U[0] + base)[x] = c0;
         return;
     }
     const bool leads = fresh || a.lead_mode[b] != (narrow_cells(st) ? 1 : 2);
+    const bool row0 = !(st == GALV_INSTANCE_OK_FAST_U32 && a.synth_l1 && a.L > 1);
+    if (!leads && !row0) return;                   // the usual case after a handle's first solve
     const uint64_t cs = a.ck[((int64_t)b * a.L) * a.S_pad + s];
     if (narrow_cells(st)) {
         uint32_t *u0 = reinterpret_cast<uint32_t *>(a.U[0] + base);
         uint32_t *u1 = reinterpret_cast<uint32_t *>(a.U[1] + base);
-        if (x < a.lead) {
-            if (leads) {
+        if (leads)
+            for (int64_t x = x0; x < a.lead; x += step) {
                 u0[x] = Narrow::infinity();
                 u1[x] = Narrow::infinity();
             }
-        } else if (!(st == GALV_INSTANCE_OK_FAST_U32 && a.synth_l1 && a.L > 1)) {
-            u0[x] = Narrow::first_layer(cs);
-        }
+        if (row0)
+            for (int64_t x = a.lead + x0; x < a.row; x += step) u0[x] = Narrow::first_layer(cs);
     } else {
         double *u0 = reinterpret_cast<double *>(a.U[0] + base);
         double *u1 = reinterpret_cast<double *>(a.U[1] + base);
-        if (x < a.lead) {
-            if (leads) {
+        if (leads)
+            for (int64_t x = x0; x < a.lead; x += step) {
                 u0[x] = Wide::infinity();
                 u1[x] = Wide::infinity();
             }
-        } else {
-            u0[x] = Wide::first_layer(cs);
-        }
+        for (int64_t x = a.lead + x0; x < a.row; x += step) u0[x] = Wide::first_layer(cs);
     }
 }
 
@@ -1294,11 +1292,42 @@ __global__ __launch_bounds__(kThreads) void stats_kernel(Layout a, int64_t *out)
     }
 }
 
-// One thread per instance, from the full budget and the stored best last strategy.
+// One wave per instance, from the full budget and the stored best last strategy.  The walk is
+// a chain of dependent loads, two per layer (the memory of the chosen strategy, then the
+// back-pointer it leads to); when the instance's memory table fits LDS the wave copies it there
+// first, coalesced, which leaves one global load per layer in the chain.
+constexpr int kWalkLds = 16384;                  // int32 words of m(l, s) kept in LDS
 __global__ __launch_bounds__(kWave) void backtrack_kernel(Layout a, int32_t *plan) {
-    const int b = blockIdx.x * kWave + threadIdx.x;
-    if (b >= a.B) return;
-    walk_plan(a, b, a.budget[b], a.last[b], plan + (int64_t)b * a.L);
+    const int b = blockIdx.x;
+    __shared__ int32_t m_lds[kWalkLds];
+    const int64_t n = (int64_t)a.L * a.S;
+    const int32_t *m = a.m + (int64_t)b * n;
+    const bool in_lds = n <= kWalkLds;
+    int s = a.last[b];
+    if (in_lds && s >= 0)
+        for (int64_t i = threadIdx.x; i < n; i += kWave) m_lds[i] = m[i];
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    int32_t *out = plan + (int64_t)b * a.L;
+    if (!in_lds || s < 0) {
+        walk_plan(a, b, a.budget[b], s, out);
+        return;
+    }
+    int64_t e = a.budget[b];
+    for (int l = a.L - 1; l >= 1; --l) {
+        out[l] = s;
+        e -= m_lds[(int64_t)l * a.S + s];
+        if (e < 0 || e > a.E_max) {             // cannot happen for a reachable cell; keeps the walk inside the table
+            for (int q = 0; q < a.L; ++q) out[q] = -1;
+            return;
+        }
+        s = load_bp(a, (((int64_t)b * (a.L - 1) + (l - 1)) * a.S + s) * a.e_pad + e);
+        if (s < 0 || s >= a.S) {
+            for (int q = 0; q < a.L; ++q) out[q] = -1;
+            return;
+        }
+    }
+    out[0] = s;
 }
 
 // min_s C[L-1][e][s] and the lowest minimising s for one (instance, budget column).
@@ -1709,8 +1738,12 @@ galv_status_t enqueue_solve(galv_dp *h, const int64_t *c_dev, const int32_t *m_d
         h->lds_allowed = true;
     }
     prep_kernel<<<a.B, kThreads, 0, st>>>(a, h->desc.flags);
-    init_kernel<<<dim3((unsigned)((a.row + kThreads - 1) / kThreads), a.S, a.B), kThreads, 0, st>>>(
-        a, h->fresh ? 1 : 0);
+    {
+        // at most 16 cells per thread: enough blocks to write a row at full rate, few enough to cost
+        // nothing when, as usual after a handle's first solve, there is nothing to write
+        const int64_t blocks = (a.row + 16 * kThreads - 1) / (16 * kThreads);
+        init_kernel<<<dim3((unsigned)blocks, a.S, a.B), kThreads, 0, st>>>(a, h->fresh ? 1 : 0);
+    }
     a.b_off = 0;
     a.b_step = 1;
     if (h->n_side <= 1 || a.L < 2) {
@@ -1870,8 +1903,7 @@ galv_status_t galv_dp_backtrack(galv_dp_t *h, int32_t *plan_dev, void *stream) {
     if (!plan_dev) return fail(GALV_ERR_INVALID_ARG, "plan_dev is NULL");
     if (!h->solved) return fail(GALV_ERR_STATE, "backtrack before a successful solve");
     const Layout &a = h->lay;
-    backtrack_kernel<<<(a.B + kWave - 1) / kWave, kWave, 0, static_cast<hipStream_t>(stream)>>>(
-        a, plan_dev);
+    backtrack_kernel<<<a.B, kWave, 0, static_cast<hipStream_t>(stream)>>>(a, plan_dev);
     HIP_TRY(hipGetLastError());
     return GALV_OK;
 }
@@ -1915,7 +1947,7 @@ galv_status_t galv_dp_solve_static(const galv_dp_desc_t *desc, const int64_t *c_
     hipStream_t st = static_cast<hipStream_t>(stream);
     rc = enqueue_solve(&h, c_dev, m_dev, R_dev, r_idx_dev, budget_dev, best_cost_dev, best_last_dev, st);
     if (rc != GALV_OK) return rc;
-    backtrack_kernel<<<(h.lay.B + kWave - 1) / kWave, kWave, 0, st>>>(h.lay, plan_dev);
+    backtrack_kernel<<<h.lay.B, kWave, 0, st>>>(h.lay, plan_dev);
     HIP_TRY(hipGetLastError());
     return GALV_OK;
 }
