@@ -313,7 +313,9 @@ def run_config(cfg, args, torch, binding, workloads):
                                                        args.steps, args.warmup)
     # Share of the min-plus candidates the sweep evaluated: on the 32-bit-key path rows that cannot
     # win any minimum of a tile are left out (the library counts rows reduced / rows listed).
-    share = [float(r) / float(n) if n > 0 else 1.0 for r, n in stats]
+    share = [float(r) / float(n) if n > 0 else 1.0 for r, n, _ in stats]
+    fetched_share = (float(sum(f for _, _, f in stats)) / float(sum(n for _, n, _ in stats))
+                     if sum(n for _, n, _ in stats) > 0 else 1.0)
     # lane-ops of one layer: per instance and table state the fixed work of its path, plus its
     # (E_b + 1) * S^2 candidates, as far as they were evaluated, times the path's cost per candidate
     lane_ops_per_layer = sum((FIXED_OPS_PER_STATE.get(int(st), 0.0) +
@@ -383,6 +385,7 @@ def run_config(cfg, args, torch, binding, workloads):
         "searches_per_sec": w.B / (ms_per_step * 1e-3),
         "exact_candidates_per_sec": exact / (ms_per_step * 1e-3),
         "candidates_evaluated_share": evaluated / max(1.0, exact / n_layer_steps),
+        "cost_rows_fetched_share": fetched_share,
         "solve_ms_median": solve_ms[len(solve_ms) // 2],
         "instances_by_path": {"u32_keys": int((status == binding.GALV_INSTANCE_OK_FAST_U32).sum()),
                               "f64_keys_32bit_cells": int((status == binding.GALV_INSTANCE_OK_FAST).sum()),

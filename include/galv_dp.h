@@ -83,6 +83,14 @@ typedef struct {
 
 #define GALV_DP_NO_U32 4u      /* do not use the 32-bit integer-key kernels (see
                                   GALV_INSTANCE_OK_FAST_U32); the 64-bit-key ones take over   */
+#define GALV_DP_NO_PEEK 8u     /* always fetch every usable former-layer row (see below)          */
+#define GALV_DP_FORCE_PEEK 16u /* 32-bit-key sweep: look at a row's cells in a tile's first and last
+                                  column before fetching the row, and skip the fetch when they show
+                                  that the row cannot win any minimum of the tile.  By default this
+                                  is done when a layer has enough workgroups to fill the chip (the
+                                  sweep is then bound by bytes; below that it is bound by latency
+                                  and the extra dependent step costs more than it saves).  Results
+                                  are identical either way.                                          */
 #define GALV_DP_STREAMS_SHIFT 8 /* bits 8..12: how many internal streams the layer sweeps are   */
 #define GALV_DP_STREAMS_MASK 0x1f00u /* spread over; 0 = chosen from the shape, 1 = none, at most 16 */
 #define GALV_DP_STREAMS(n) ((uint32_t)(n) << GALV_DP_STREAMS_SHIFT)
@@ -201,11 +209,14 @@ galv_status_t galv_dp_get_status(galv_dp_t *h, int32_t *status_dev, void *stream
 
 /*
  * Work statistics of the last solve, for instances on the 32-bit-key path (zeros otherwise):
- *   stats_dev [B][2] int64  [b][0] former-layer rows actually reduced, [b][1] usable rows listed,
- *                           both summed over the budget tiles and the layers 1..L-1.
+ *   stats_dev [B][3] int64  [b][0] former-layer rows actually reduced, [b][1] usable rows listed,
+ *                           [b][2] rows fetched from the cost table, each summed over the budget
+ *                           tiles and the layers 1..L-1.
  * The sweep leaves out rows that cannot win any minimum of a tile (cost above the column minimum
- * by more than the largest transition cost, in every column of the tile); [b][0] / [b][1] is the
- * share of the min-plus candidates of Eq. 1 that was evaluated.  Results do not depend on it.
+ * by more than the largest transition cost, in every column of the tile), and does not even fetch
+ * a row when two of its cells show as much; [b][0] / [b][1] is the share of the min-plus
+ * candidates of Eq. 1 that was evaluated, [b][2] / [b][1] the share of the cost cells that was
+ * read.  Results do not depend on either.
  */
 galv_status_t galv_dp_get_stats(galv_dp_t *h, int64_t *stats_dev, void *stream);
 

@@ -24,6 +24,8 @@ GALV_ERR_INVALID_ARG, GALV_ERR_WORKSPACE, GALV_ERR_RANGE, GALV_ERR_HIP, GALV_ERR
 GALV_DP_FORCE_INT64 = 1
 GALV_DP_BP_U8 = 2
 GALV_DP_NO_U32 = 4
+GALV_DP_NO_PEEK = 8
+GALV_DP_FORCE_PEEK = 16
 
 
 def GALV_DP_STREAMS(n: int) -> int:
@@ -304,8 +306,8 @@ class Solver:
         return st
 
     def stats(self, stream=None):
-        """[B][2] int64: rows reduced, rows listed (32-bit-key instances; see galv_dp_get_stats)."""
-        st = torch.empty((self.B, 2), dtype=torch.int64, device=self.device)
+        """[B][3] int64: rows reduced, rows listed, rows fetched (32-bit-key instances; see galv_dp_get_stats)."""
+        st = torch.empty((self.B, 3), dtype=torch.int64, device=self.device)
         galv_dp_get_stats(self.handle, st, stream)
         return st
 

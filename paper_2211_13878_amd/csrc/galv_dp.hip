@@ -117,6 +117,7 @@ struct Layout {
     char *U[2];           // rolling cost rows   [B][S_pad][row] of 8-byte slots
     void *bp;             // argmin, un-shifted  [B][L-1][S][e_pad] of int32, or of uint8 (0xFF = none)
     int32_t bp_u8;        // 1: one-byte back-pointers
+    int32_t peek;         // 1: the row-sharing sweep looks at two cells of a row before it fetches the row
     int32_t synth_l1;     // 1: the 32-bit-key sweep makes up layer 0's cells (a constant per strategy)
                           //    when it sweeps layer 1, so layer 0's row is never written nor read
     int32_t b_off, b_step; // a sweep launch covers instances b_off + z * b_step (dealt over streams)
@@ -129,7 +130,7 @@ struct Layout {
     int32_t *status;      // per instance        [B]
     int32_t *last;        // best last strategy  [B]
     int32_t *lead_mode;   // whose infinity leads the rows hold: 1 narrow, 2 wide, 0 none  [B]
-    uint32_t *stats;      // 32-bit-key sweeps: rows reduced << 16 | rows listed, per tile  [B][L-1][n_tiles]
+    uint32_t *stats;      // 32-bit-key sweeps, per tile: rows reduced << 16 | rows listed; rows fetched  [B][L-1][n_tiles][2]
     const int64_t *c;
     const int32_t *m;
     const int64_t *R;
@@ -837,9 +838,12 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int bud
         return Up + (int64_t)(uint32_t)ent * pitch - (int64_t)(ent >> 32);
     };
 
-    if (s0 == 0 && esub == 0 && lane == 0)         // statistics: this body reduces every listed row
-        a.stats[((int64_t)b * (a.L - 1) + (l - 1)) * a.n_tiles + (uint32_t)tile_start / (uint32_t)a.tile_e] =
-            (uint32_t)n << 16 | (uint32_t)n;
+    if (s0 == 0 && esub == 0 && lane == 0) {       // statistics: this body reads and reduces every listed row
+        uint32_t *st = a.stats + 2 * (((int64_t)b * (a.L - 1) + (l - 1)) * a.n_tiles +
+                                      (uint32_t)tile_start / (uint32_t)a.tile_e);
+        st[0] = (uint32_t)n << 16 | (uint32_t)n;
+        st[1] = (uint32_t)n;
+    }
     if (n > 0) {
         // Pass 1: the column minima of the former layer.  Pure loads: batches of kBatch list
         // entries, the next batch requested before the current one is reduced.
@@ -1029,13 +1033,95 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
     for (int j = 0; j < TE; ++j) cmin[j] = 0xffffffffu;
 
     if (g == 0 && lane == 0) count[0] = 0;
+
+    // Peek.  Every stored row is non-increasing along the budget axis (more memory never costs
+    // more), so a row's cells in this tile lie between its cell in the tile's last column (the
+    // smallest) and its cell in the first column (the largest), and the column minima are at
+    // most Cmin_first = the minimum over the rows' first-column cells.  A row whose LAST-column
+    // cell is at least Cmin_first + dmax is therefore clamped in every column of the tile and
+    // need not be read at all: two cells per row (scalar loads) decide whether its 64 * TE cells
+    // are fetched.  The row that attains a column's minimum always passes (its cell there is at
+    // most Cmin_first), so the minima over the rows that are read are the true column minima.
+    uint32_t keep = 0;                             // bit r: row g + NG * r is read (wave-uniform)
+    if (n > 0 && !a.peek) {
+        // (a launch that does not fill the chip is bound by latency, not by bytes: there the two
+        // extra dependent steps of the peek cost more than the rows it saves)
+#pragma unroll
+        for (int r = 0; r < TS; ++r)
+            if (g + NG * r < n) keep |= 1u << r;
+        if (g == 0 && lane == 0) count[2] = (uint32_t)n;
+    }
+    if (n > 0 && a.peek) {
+        // One gather for the whole wave: lane r (r < TS) fetches row r's cell in the tile's first
+        // column, lane 32 + r its cell in the last column.  The rows' addresses are wave-uniform
+        // scalars; each lane picks its own with a chain of selects.
+        uint32_t last_c[TS];
+        uint32_t first_min = 0xffffffffu;
+        static_assert(TS <= 32, "one lane per row and boundary");
+        const int my_row = lane & 31;
+        const bool my_last = lane >= 32;
+        const uint32_t *my_p = Up;                 // any valid address for the idle lanes
+        uint32_t my_c0 = 0;
+        bool my_below = false;                     // (first layer) this lane's column lies below the row's shift
+#pragma unroll
+        for (int r = 0; r < TS; ++r) {
+            const uint64_t ent = vl[g + NG * r];
+            const uint32_t sp = (uint32_t)ent, shift = (uint32_t)(ent >> 32);
+            if (first) {
+                const uint32_t c0 = (uint32_t)ck0[sp];
+                if (my_row == r) {
+                    my_c0 = c0;
+                    my_below = tile_start + (my_last ? kCols - 1 : 0) < (int64_t)shift;
+                }
+            } else {
+                const uint32_t *p = Up + (int64_t)sp * pitch - (int64_t)shift;
+                if (my_row == r) my_p = p;
+            }
+        }
+        uint32_t mine;
+        if (first)
+            mine = my_below ? kInf32 : my_c0;
+        else
+            mine = my_p[my_last ? kCols - 1 : 0];
+#pragma unroll
+        for (int r = 0; r < TS; ++r) {
+            first_min = min(first_min, (uint32_t)__builtin_amdgcn_readlane((int)mine, r));
+            last_c[r] = (uint32_t)__builtin_amdgcn_readlane((int)mine, 32 + r);
+        }
+        uint32_t *peek = count + 2;                // [0]: rows read, then behind the list: the waves' minima
+        uint32_t *wave_min = keys + kKeep * kCols; // [NG]
+        if (lane == 0) wave_min[g] = first_min;
+        if (g == 0 && lane == 0) peek[0] = 0;
+        __syncthreads();
+        uint32_t cmin_first = 0xffffffffu;
+#pragma unroll
+        for (int w = 0; w < NG; ++w) cmin_first = min(cmin_first, (uint32_t)uniform((int)wave_min[w]));
+        // an unreachable first column (Cmin_first = infinity) bounds nothing: read every row
+        const uint32_t limit = cmin_first < kInf32 ? cmin_first + dmax : 0xffffffffu;
+        int mine_read = 0;
+#pragma unroll
+        for (int r = 0; r < TS; ++r)
+            if (g + NG * r < n && last_c[r] < limit) {
+                keep |= 1u << r;
+                ++mine_read;
+            }
+        if (lane == 0 && mine_read) atomicAdd(&peek[0], (uint32_t)mine_read);
+    }
+
     uint32_t rowc[TS][TE];
     if (n > 0) {                                   // workgroup-uniform
         uint32_t pm[TE];
 #pragma unroll
         for (int j = 0; j < TE; ++j) pm[j] = 0xffffffffu;
 #pragma unroll
-        for (int r = 0; r < TS; ++r) load_row(vl[g + NG * r], rowc[r]);
+        for (int r = 0; r < TS; ++r) {
+            if (keep >> r & 1) {
+                load_row(vl[g + NG * r], rowc[r]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < TE; ++j) rowc[r][j] = 0xffffffffu;       // leaves every minimum alone
+            }
+        }
 #pragma unroll
         for (int r = 0; r < TS; ++r)
 #pragma unroll
@@ -1052,7 +1138,7 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
 #pragma unroll
         for (int r = 0; r < TS; ++r) {
             const int i = g + NG * r;
-            if (i < n) {                           // the padding repeats a row that is listed already
+            if (keep >> r & 1) {                   // listed (the padding repeats a listed row) and read
                 uint32_t d[TE];
                 bool live = false;
 #pragma unroll
@@ -1078,9 +1164,12 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
     if (s0 >= S) return;                           // an idle strategy group has done its share of the rows
 
     const int nsurv = n > 0 ? uniform((int)count[0]) : 0;
-    if (g == 0 && lane == 0)                       // statistics: how much the pruning removed
-        a.stats[((int64_t)b * (a.L - 1) + (l - 1)) * a.n_tiles + (uint32_t)tile_start / (uint32_t)a.tile_e] =
-            (uint32_t)(nsurv <= kKeep ? nsurv : n) << 16 | (uint32_t)n;
+    if (g == 0 && lane == 0) {                     // statistics: how much the pruning removed
+        uint32_t *st = a.stats + 2 * (((int64_t)b * (a.L - 1) + (l - 1)) * a.n_tiles +
+                                      (uint32_t)tile_start / (uint32_t)a.tile_e);
+        st[0] = (uint32_t)(nsurv <= kKeep ? nsurv : n) << 16 | (uint32_t)n;
+        st[1] = n > 0 ? count[2] : 0u;             // rows fetched
+    }
     if (nsurv > 0) {
         const bool pruned = nsurv <= kKeep;        // workgroup-uniform
         const int nrow = pruned ? nsurv : n;
@@ -1266,30 +1355,28 @@ __device__ __forceinline__ void walk_plan(const Layout &a, int b, int64_t e, int
 // and the layers; zeros for an instance that is not on the 32-bit-key path.
 __global__ __launch_bounds__(kThreads) void stats_kernel(Layout a, int64_t *out) {
     const int b = blockIdx.x;
-    __shared__ unsigned long long red[2][kThreads];
-    unsigned long long done = 0, listed = 0;
+    __shared__ unsigned long long red[3][kThreads];
+    unsigned long long done = 0, listed = 0, fetched = 0;
     if (a.status[b] == GALV_INSTANCE_OK_FAST_U32) {
         const int nt = a.budget[b] / a.tile_e + 1;
         for (int64_t i = threadIdx.x; i < (int64_t)(a.L - 1) * nt; i += kThreads) {
-            const uint32_t v = a.stats[((int64_t)b * (a.L - 1) + i / nt) * a.n_tiles + i % nt];
-            done += v >> 16;
-            listed += v & 0xffffu;
+            const uint32_t *v = a.stats + 2 * (((int64_t)b * (a.L - 1) + i / nt) * a.n_tiles + i % nt);
+            done += v[0] >> 16;
+            listed += v[0] & 0xffffu;
+            fetched += v[1];
         }
     }
     red[0][threadIdx.x] = done;
     red[1][threadIdx.x] = listed;
+    red[2][threadIdx.x] = fetched;
     __syncthreads();
     for (int w = kThreads / 2; w > 0; w >>= 1) {
-        if ((int)threadIdx.x < w) {
-            red[0][threadIdx.x] += red[0][threadIdx.x + w];
-            red[1][threadIdx.x] += red[1][threadIdx.x + w];
-        }
+        if ((int)threadIdx.x < w)
+            for (int q = 0; q < 3; ++q) red[q][threadIdx.x] += red[q][threadIdx.x + w];
         __syncthreads();
     }
-    if (threadIdx.x == 0) {
-        out[2 * b] = (int64_t)red[0][0];
-        out[2 * b + 1] = (int64_t)red[1][0];
-    }
+    if (threadIdx.x == 0)
+        for (int q = 0; q < 3; ++q) out[3 * b + q] = (int64_t)red[q][0];
 }
 
 // One wave per instance, from the full budget and the stored best last strategy.  The walk is
@@ -1562,7 +1649,7 @@ struct VariantEntry {
 };
 template <int TS, int TE, int NG, int WPE, int W, int UX, int SHARE>
 VariantEntry variant_entry() {
-    static_assert((W == 1 || W == 2 || W == 3 || W == 4 || W == 6 || W == 8) && W % NG == 0,
+    static_assert((W == 1 || W == 2 || W == 3 || W == 4 || W == 6 || W == 8 || W == 16) && W % NG == 0,
                   "strategy groups must divide the workgroup's waves");
     static_assert(!SHARE || W == NG, "the row-sharing body has one budget tile per workgroup");
     static_assert((UX == 1 || UX == 2) && TE * UX <= 4, "budget columns per lane");
@@ -1623,7 +1710,8 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     if (d->n_strategies > kMaxS)
         return fail(GALV_ERR_INVALID_ARG, "n_strategies %d exceeds the limit %d", d->n_strategies,
                     kMaxS);
-    if (d->flags & ~(GALV_DP_FORCE_INT64 | GALV_DP_BP_U8 | GALV_DP_NO_U32 | GALV_DP_STREAMS_MASK))
+    if (d->flags & ~(GALV_DP_FORCE_INT64 | GALV_DP_BP_U8 | GALV_DP_NO_U32 | GALV_DP_NO_PEEK | GALV_DP_FORCE_PEEK |
+                     GALV_DP_STREAMS_MASK))
         return fail(GALV_ERR_INVALID_ARG, "unknown flag bits");
     if (((d->flags & GALV_DP_STREAMS_MASK) >> GALV_DP_STREAMS_SHIFT) > (uint32_t)kMaxSide)
         return fail(GALV_ERR_INVALID_ARG, "at most %d internal streams", kMaxSide);
@@ -1655,16 +1743,20 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     while ((1 << k) < a.S) ++k;
     a.k_bits = k;
     a.tile_e = kWave * v.te * v.ux * (v.w / v.ng);
-    // row-sharing body: partial minima [NG][columns], count, then keep_rows rows of (strategy index, keys)
+    // row-sharing body: partial minima [NG][columns], counters, keep_rows rows of (strategy index, keys), [NG] minima
     p->lds_bytes = 0;
     if (v.share) {
         const size_t cols = (size_t)kWave * v.te * v.ux, keep = keep_rows(v.ts * v.ng);
-        p->lds_bytes = (unsigned)(((size_t)v.ng * cols + 4 + keep + keep * cols) * sizeof(uint32_t));
+        p->lds_bytes = (unsigned)(((size_t)v.ng * cols + 4 + keep + keep * cols + v.ng) * sizeof(uint32_t));
     }
     if (p->lds_bytes > 160u * 1024u)
         return fail(GALV_ERR_RANGE, "internal: staging variant needs %u bytes of LDS", p->lds_bytes);
     a.e_pad = (int64_t)round_up((size_t)a.E_max + 1, kEAlign);
     a.n_tiles = (int32_t)((a.E_max + a.tile_e) / a.tile_e);   // ceil((E_max+1)/tile_e)
+    // measured: with ~1000 workgroups per layer (config 1) the peek costs 9 %, with ~6000 (config 2) it gains 14 %
+    a.peek = (int64_t)a.n_tiles * a.B >= 3072 ? 1 : 0;
+    if (d->flags & GALV_DP_NO_PEEK) a.peek = 0;
+    if (d->flags & GALV_DP_FORCE_PEEK) a.peek = 1;
     a.lead = (int64_t)round_up((size_t)a.E_max + 1, 64);
     a.row = a.lead + a.e_pad;
     p->var = v;
@@ -1694,7 +1786,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     p->off_last = take((size_t)a.B * sizeof(int32_t));
     p->off_dclamp = take((size_t)a.B * sizeof(uint32_t));
     p->off_lead_mode = take((size_t)a.B * sizeof(int32_t));
-    p->off_stats = take((size_t)a.B * (a.L > 1 ? a.L - 1 : 1) * a.n_tiles * sizeof(uint32_t));
+    p->off_stats = take((size_t)a.B * (a.L > 1 ? a.L - 1 : 1) * a.n_tiles * 2 * sizeof(uint32_t));
     p->total = off;
     return GALV_OK;
 }

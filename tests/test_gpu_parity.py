@@ -300,7 +300,7 @@ def test_random_shapes_ragged_tiles(S):
                                   c_range=(0, 50), r_range=(0, 20), infeasible=0.08,
                                   zero_diagonal=False)
     w.budget[0] = E_max
-    for flags in ALL_PATHS:
+    for flags in ALL_PATHS + (binding.GALV_DP_FORCE_PEEK,):
         check_against_oracle(w, flags=flags, table_instances=[0, 1, 2])
 
 
@@ -309,7 +309,7 @@ def test_degenerate_sizes():
         w = workloads.random_workload(7, 4, L, S, E, m_range=(0, 3), c_range=(0, 5),
                                       r_range=(0, 5))
         w.budget[0] = E                     # at least one instance at the full width
-        for flags in ALL_PATHS:
+        for flags in ALL_PATHS + (binding.GALV_DP_FORCE_PEEK,):
             check_against_oracle(w, flags=flags, table_instances=range(4))
 
 

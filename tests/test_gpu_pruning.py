@@ -17,6 +17,9 @@ from test_gpu_parity import check_against_oracle
 pytestmark = pytest.mark.gpu
 
 
+PEEK, NO_PEEK = binding.GALV_DP_FORCE_PEEK, binding.GALV_DP_NO_PEEK
+
+
 def reduced_share(w, flags=0):
     sol = binding.Solver(w.B, w.L, w.S, w.E_max, w.nR, flags)
     sol.solve(*binding.upload(w))
@@ -34,9 +37,12 @@ def test_nothing_can_be_pruned(S):
     w = workloads.random_workload(300 + S, 3, 5, S, 700, nR=2, m_range=(0, 150), c_range=(0, 9),
                                   r_range=(1000, 5000), infeasible=0.05, zero_diagonal=False)
     w.budget[0] = 700
-    check_against_oracle(w, table_instances=[0, 1, 2], expect_status=binding.GALV_INSTANCE_OK_FAST_U32)
-    st, _ = reduced_share(w)
+    for flags in (PEEK, NO_PEEK):
+        check_against_oracle(w, flags=flags, table_instances=[0, 1, 2], expect_status=binding.GALV_INSTANCE_OK_FAST_U32)
+    st, _ = reduced_share(w, PEEK)
     assert (st[:, 1] > 0).all() and (st[:, 0] >= 0.85 * st[:, 1]).all()     # all but the tiles at the unreachable low budgets
+    # the full loop re-reads, through the caches, even the few rows the first fetch had skipped
+    assert (st[:, 2] >= 0.85 * st[:, 1]).all() and (st[:, 2] <= st[:, 1]).all()
 
 
 @pytest.mark.parametrize("S", [8, 22, 44, 128])
@@ -46,9 +52,15 @@ def test_nearly_everything_is_pruned(S):
     w = workloads.random_workload(400 + S, 3, 6, S, 900, nR=2, m_range=(0, 120), c_range=(0, 100000),
                                   r_range=(0, 90), infeasible=0.05, zero_diagonal=False)
     w.budget[0] = 900
-    check_against_oracle(w, table_instances=[0, 1, 2], expect_status=binding.GALV_INSTANCE_OK_FAST_U32)
-    st, _ = reduced_share(w)
+    for flags in (PEEK, NO_PEEK):
+        check_against_oracle(w, flags=flags, table_instances=[0, 1, 2], expect_status=binding.GALV_INSTANCE_OK_FAST_U32)
+    st, _ = reduced_share(w, NO_PEEK)
+    assert (st[:, 2] == st[:, 1]).all()             # every listed row fetched
+    st, _ = reduced_share(w, PEEK)
     assert (st[:, 0] < 0.5 * st[:, 1]).all()
+    # most rows are not even fetched (instance 0 has the full budget; a tile whose first column is
+    # unreachable, as in the small-budget instances, has to fetch every row)
+    assert (st[:, 2] >= st[:, 0]).all() and st[0, 2] < 0.8 * st[0, 1]
 
 
 @pytest.mark.parametrize("seed", range(4))
@@ -60,15 +72,15 @@ def test_mixtures_around_the_list_capacity(seed):
     spread = int(rng.choice([300, 1000, 3000]))
     w = workloads.random_workload(500 + seed, 3, 6, S, 1200, nR=2, m_range=(0, 200), c_range=(0, spread),
                                   r_range=(0, 400), infeasible=0.08, zero_diagonal=False)
-    check_against_oracle(w, table_instances=[0, 1, 2])
-    for flags in (binding.GALV_DP_BP_U8, binding.GALV_DP_STREAMS(3)):
+    check_against_oracle(w, flags=PEEK, table_instances=[0, 1, 2])
+    for flags in (NO_PEEK, PEEK | binding.GALV_DP_BP_U8, PEEK | binding.GALV_DP_STREAMS(3)):
         check_against_oracle(w, flags=flags, table_instances=[1])
 
 
 def test_statistics_on_a_named_configuration_and_on_other_paths():
     w = workloads.config(1)
-    st, status = reduced_share(w)
+    st, status = reduced_share(w, PEEK)
     assert (status == binding.GALV_INSTANCE_OK_FAST_U32).all()
-    assert (st[:, 1] > 0).all() and (st[:, 0] < 0.3 * st[:, 1]).all()
+    assert (st[:, 1] > 0).all() and (st[:, 0] < 0.3 * st[:, 1]).all() and (st[:, 2] < 0.6 * st[:, 1]).all()
     st, status = reduced_share(workloads.config(1, 2), binding.GALV_DP_NO_U32)
     assert (status == binding.GALV_INSTANCE_OK_FAST).all() and (st == 0).all()

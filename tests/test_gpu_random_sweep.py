@@ -13,7 +13,8 @@ pytestmark = pytest.mark.gpu
 
 FLAGS = [0, binding.GALV_DP_NO_U32, binding.GALV_DP_FORCE_INT64, binding.GALV_DP_BP_U8,
          binding.GALV_DP_BP_U8 | binding.GALV_DP_NO_U32, binding.GALV_DP_STREAMS(3),
-         binding.GALV_DP_STREAMS(3) | binding.GALV_DP_BP_U8]
+         binding.GALV_DP_STREAMS(3) | binding.GALV_DP_BP_U8,
+         binding.GALV_DP_FORCE_PEEK, binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_BP_U8 | binding.GALV_DP_STREAMS(2)]
 
 
 @pytest.mark.parametrize("seed", [11, 12, 13])
