@@ -1035,13 +1035,15 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
     if (g == 0 && lane == 0) count[0] = 0;
 
     // Peek.  Every stored row is non-increasing along the budget axis (more memory never costs
-    // more), so a row's cells in this tile lie between its cell in the tile's last column (the
-    // smallest) and its cell in the first column (the largest), and the column minima are at
-    // most Cmin_first = the minimum over the rows' first-column cells.  A row whose LAST-column
-    // cell is at least Cmin_first + dmax is therefore clamped in every column of the tile and
-    // need not be read at all: two cells per row (scalar loads) decide whether its 64 * TE cells
-    // are fetched.  The row that attains a column's minimum always passes (its cell there is at
-    // most Cmin_first), so the minima over the rows that are read are the true column minima.
+    // more), so a row's cells in this tile are at least its cell in the tile's last column, and
+    // every column minimum of the tile is at most Cmin_before = the minimum over the rows' cells
+    // in the column just BEFORE the tile.  A row whose last-column cell is at least
+    // Cmin_before + dmax is therefore clamped in every column of the tile and need not be read at
+    // all: two cells per row decide whether its 64 * TE cells are fetched.  (The column before the
+    // tile rather than its first column: that is the last column of the neighbouring tile, whose
+    // workgroup probes the same cell, so the two probes meet in the L2.)  The row that attains a
+    // column's minimum always passes (its cell there is at most Cmin_before), so the minima over
+    // the rows that are read are the true column minima.
     uint32_t keep = 0;                             // bit r: row g + NG * r is read (wave-uniform)
     if (n > 0 && !a.peek) {
         // (a launch that does not fill the chip is bound by latency, not by bytes: there the two
@@ -1052,8 +1054,8 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
         if (g == 0 && lane == 0) count[2] = (uint32_t)n;
     }
     if (n > 0 && a.peek) {
-        // One gather for the whole wave: lane r (r < TS) fetches row r's cell in the tile's first
-        // column, lane 32 + r its cell in the last column.  The rows' addresses are wave-uniform
+        // One gather for the whole wave: lane r (r < TS) fetches row r's cell in the column before
+        // the tile (for the first tile that is the infinity lead), lane 32 + r its cell in the last column.  The rows' addresses are wave-uniform
         // scalars; each lane picks its own with a chain of selects.
         uint32_t last_c[TS];
         uint32_t first_min = 0xffffffffu;
@@ -1071,7 +1073,7 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
                 const uint32_t c0 = (uint32_t)ck0[sp];
                 if (my_row == r) {
                     my_c0 = c0;
-                    my_below = tile_start + (my_last ? kCols - 1 : 0) < (int64_t)shift;
+                    my_below = tile_start + (my_last ? kCols - 1 : -1) < (int64_t)shift;
                 }
             } else {
                 const uint32_t *p = Up + (int64_t)sp * pitch - (int64_t)shift;
@@ -1082,7 +1084,7 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
         if (first)
             mine = my_below ? kInf32 : my_c0;
         else
-            mine = my_p[my_last ? kCols - 1 : 0];
+            mine = my_p[my_last ? kCols - 1 : -1];
 #pragma unroll
         for (int r = 0; r < TS; ++r) {
             first_min = min(first_min, (uint32_t)__builtin_amdgcn_readlane((int)mine, r));
