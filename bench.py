@@ -140,6 +140,10 @@ def main():
     ap.add_argument("--alg1", default=None, metavar="LAYERS,DEVICES,BUDGET",
                     help="instead of the main benchmark: time Algorithm 1 (windowed driver over the batched "
                          "solver) on a seeded synthetic cost model and the plain oracle loop beside it")
+    ap.add_argument("--r-scale", type=int, default=1,
+                    help="multiply every transition cost by this factor (not the named configuration any more): "
+                         "with transition costs far above the spread of the layer costs nothing can be pruned, "
+                         "which is the sweep's worst case")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic: 1 GiB read, "
                          "1 GiB written) so that rocprofv3 FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -242,6 +246,9 @@ def main():
 def run_config(cfg, args, torch, binding, workloads):
     """Time one named configuration; returns its record (the JSON line's fields)."""
     w = workloads.config(cfg)
+    if args.r_scale != 1:
+        w.R = w.R * args.r_scale
+        w.name += f" with R x {args.r_scale}"
     base_flags = ((binding.GALV_DP_FORCE_INT64 if args.force_int64 else 0) |
                   (binding.GALV_DP_NO_U32 if args.no_u32 else 0) |
                   (binding.GALV_DP_BP_U8 if args.bp_u8 else 0))
