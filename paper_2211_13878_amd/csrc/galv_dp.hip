@@ -953,7 +953,7 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int bud
 // `cap` strategies (host and device agree through this one function).
 constexpr int keep_rows(int cap) { return cap <= 64 ? 16 : 32; }
 
-// Row-sharing form of the 32-bit-key body, for S <= TS * NG with one budget tile of
+// Row-sharing form of the 32-bit-key body, for S <= TS * NG (up to 256) with one budget tile of
 // 64 * TE columns per workgroup of NG waves.  Wave g owns the former-layer rows g, g + NG, ...
 // (TS of them, in registers) AND the strategy group g of the output.
 //   1. Every wave loads its rows once (shifted, coalesced) and reduces them to partial column
@@ -1502,7 +1502,8 @@ __global__ __launch_bounds__(kThreads) void export_kernel(Layout a, int b, int64
 // waves per SIMD (512 VGPRs / WPE each), W waves per workgroup, UX times the columns for
 // the 32-bit-key body, SHARE = 1 for the row-sharing 32-bit-key body (W == NG waves, each
 // owning TS rows and TS strategies of one tile of 64 * TE * UX columns; it needs
-// TS * NG >= S, so the last variant, which serves any S, uses the plain body).
+// TS * NG >= S, so the last variant, which serves any S, uses the plain body; the one before
+// it covers up to 256 strategies with 16-wave workgroups).
 // Measured on MI355X: with the dominated rows pruned the sweep is bound by HBM, and tiles of
 // 128 columns beat 64 (longer contiguous row segments) while larger register tiles gain
 // nothing; 8 waves per SIMD do not build for TS = 16 (the compiler then spills scalar
@@ -1529,7 +1530,10 @@ __global__ __launch_bounds__(kThreads) void export_kernel(Layout a, int b, int64
 #define GALV_V6 16, 2, 8, 6, 8, 1, 1
 #endif
 #ifndef GALV_V7
-#define GALV_V7 16, 2, 8, 6, 8, 1, 0
+#define GALV_V7 16, 2, 16, 4, 16, 1, 1
+#endif
+#ifndef GALV_V8
+#define GALV_V8 16, 2, 8, 6, 8, 1, 0
 #endif
 
 // ---------------------------------------------------------------------------------------------
@@ -1664,7 +1668,7 @@ const VariantEntry &pick_variant(int S) {
     static const VariantEntry table[] = {
         variant_entry<GALV_V0>(), variant_entry<GALV_V1>(), variant_entry<GALV_V2>(),
         variant_entry<GALV_V3>(), variant_entry<GALV_V4>(), variant_entry<GALV_V5>(),
-        variant_entry<GALV_V6>(), variant_entry<GALV_V7>()};
+        variant_entry<GALV_V6>(), variant_entry<GALV_V7>(), variant_entry<GALV_V8>()};
     constexpr int n = sizeof table / sizeof table[0];
     for (int i = 0; i < n; ++i)
         if (S <= table[i].v.ts * table[i].v.ng) return table[i];

@@ -289,7 +289,7 @@ def test_config4_shape_small_budget_full_tables():
 
 # ------------------------------------------------------- random shapes / edges
 
-@pytest.mark.parametrize("S", [1, 2, 5, 8, 9, 16, 22, 23, 32, 33, 37, 40, 44, 45, 64, 65, 70, 128, 130, 200])
+@pytest.mark.parametrize("S", [1, 2, 5, 8, 9, 16, 22, 23, 32, 33, 37, 40, 44, 45, 64, 65, 70, 128, 130, 200, 256, 257])
 def test_random_shapes_ragged_tiles(S):
     """Several budget tiles with a ragged tail, strategies around every kernel
     variant's group size, narrow values (many ties), m = 0, random budgets,

@@ -29,7 +29,7 @@ def reduced_share(w, flags=0):
     return st, status
 
 
-@pytest.mark.parametrize("S", [17, 22, 44, 64, 65, 100, 128])
+@pytest.mark.parametrize("S", [17, 22, 44, 64, 65, 100, 128, 129, 200, 256])
 def test_nothing_can_be_pruned(S):
     """Transition costs far above the spread of the layer costs: every row stays alive in every
     tile, more rows than the kept-row list holds (16 up to 64 strategies, 32 beyond), so the
@@ -45,7 +45,7 @@ def test_nothing_can_be_pruned(S):
     assert (st[:, 2] >= 0.85 * st[:, 1]).all() and (st[:, 2] <= st[:, 1]).all()
 
 
-@pytest.mark.parametrize("S", [8, 22, 44, 128])
+@pytest.mark.parametrize("S", [8, 22, 44, 128, 200, 256])
 def test_nearly_everything_is_pruned(S):
     """Layer costs spread over a range a thousand times the largest transition cost: a handful
     of rows survive per tile."""
@@ -68,7 +68,7 @@ def test_mixtures_around_the_list_capacity(seed):
     """Transition costs comparable to the cost spread, so that the number of surviving rows
     varies from tile to tile around the capacity of the list (some tiles pruned, some not)."""
     rng = np.random.default_rng(seed)
-    S = int(rng.choice([40, 44, 96, 128]))
+    S = int(rng.choice([40, 44, 96, 128, 180, 255]))
     spread = int(rng.choice([300, 1000, 3000]))
     w = workloads.random_workload(500 + seed, 3, 6, S, 1200, nR=2, m_range=(0, 200), c_range=(0, spread),
                                   r_range=(0, 400), infeasible=0.08, zero_diagonal=False)
