@@ -21,21 +21,25 @@
 //
 // Exact arithmetic paths, chosen per instance on the device
 // ---------------------------------------------------------
-//  * fast: cost and argmin are packed into one integer key = cost * 2^k + s'
-//    (k = ceil(log2 S)) that lives in the mantissa of a double whose exponent is
-//    pinned: K = 2^52 + key.  Adding the plain double R * 2^k + s' to a cost key
-//    and taking the floating minimum is one v_add_f64 + one v_min_f64 per
-//    candidate, exact while K stays below 2^53, and the minimum of keys is the
-//    minimum cost with the lowest s' among equals.  Two storage widths:
-//      - narrow: costs below 2^31 are stored as uint32 (infinity = 2^31), 4 bytes
-//        per table cell;
-//      - wide: the cost key itself is stored as a double (infinity = +inf).
-//  * int64: plain 64-bit integer add / compare / select with a separate index,
-//    for instances whose value range does not fit a 52-bit key.
-// A preparation kernel bounds each instance's largest possible plan cost and
-// picks the path; all paths produce bit-identical results.
+//  * 32-bit keys (small costs and transition costs: the common case): costs are taken
+//    relative to the column's smallest former cost and clamped at R_max + 1, so that
+//    key = (relative cost + R) * 2^k + s' fits 32 bits; two candidates cost two
+//    v_add_u32 and one v_min3_u32.  A clamped former strategy can neither win nor tie, which
+//    is also what lets the sweep PRUNE: a former-layer row that is clamped in every column of
+//    a tile is left out of the inner loop, and (rows being non-increasing along the budget
+//    axis) two of its cells tell whether it needs to be fetched at all.  With the usual spread
+//    of layer costs some 90-95 % of the candidates fall away and the sweep is bound by HBM.
+//  * 64-bit keys: key = cost * 2^k + s' (k = ceil(log2 S)) lives in the mantissa of a double
+//    whose exponent is pinned, K = 2^52 + key; one v_add_f64 + one v_min_f64 per candidate,
+//    exact while K stays below 2^53.  Two storage widths: narrow (costs below 2^31 stored as
+//    uint32, infinity = 2^31) and wide (the key itself stored as a double, infinity = +inf).
+//  * int64: plain 64-bit integer add / compare / select with a separate index, for
+//    instances whose value range does not fit a 52-bit key.
+// In every packed form the minimum of keys is the minimum cost with the lowest s' among
+// equals.  A preparation kernel bounds each instance's largest possible plan cost and picks
+// the path; all paths produce bit-identical results.
 //
-// All kernels are plain VALU + global memory; there is no matrix-core work in a
+// All kernels are plain VALU + LDS + global memory; there is no matrix-core work in a
 // min-plus recurrence.
 #include <hip/hip_runtime.h>
 
