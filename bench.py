@@ -56,12 +56,12 @@ HBM_PEAK_GBS = 8000.0
 # VALU lane-operations one min-plus candidate needs, by the arithmetic path of its instance
 # (status code): 32-bit keys fold two candidates into two adds and one three-way minimum;
 # 64-bit keys take one add and one minimum each; the general integer path about six.
-OPS_PER_CANDIDATE = {3: 1.5, 0: 2.0, 2: 2.0, 1: 6.0}
+OPS_PER_CANDIDATE = {3: 1.5, 4: 1.5, 0: 2.0, 2: 2.0, 1: 6.0}
 # lane-operations per table state that do not depend on the number of candidates, 32-bit-key path:
 # column minimum (1), relative cost and clamp test (2), new cell and back-pointer (4)
-FIXED_OPS_PER_STATE = {3: 7.0}
+FIXED_OPS_PER_STATE = {3: 7.0, 4: 12.0}
 # table bytes per state: cost cell read + cost cell written + int32 back-pointer written
-BYTES_PER_STATE = {3: 4 + 4 + 4, 0: 4 + 4 + 4, 2: 8 + 8 + 4, 1: 8 + 8 + 4}   # by per-instance status code
+BYTES_PER_STATE = {3: 4 + 4 + 4, 0: 4 + 4 + 4, 4: 8 + 8 + 4, 2: 8 + 8 + 4, 1: 8 + 8 + 4}   # by per-instance status code
 
 
 # HBM bytes per sweep launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by the
@@ -140,6 +140,9 @@ def main():
     ap.add_argument("--alg1", default=None, metavar="LAYERS,DEVICES,BUDGET",
                     help="instead of the main benchmark: time Algorithm 1 (windowed driver over the batched "
                          "solver) on a seeded synthetic cost model and the plain oracle loop beside it")
+    ap.add_argument("--c-scale", type=int, default=1,
+                    help="multiply every layer cost AND transition cost by this factor (not the named configuration "
+                         "any more): large costs need 64-bit table cells")
     ap.add_argument("--r-scale", type=int, default=1,
                     help="multiply every transition cost by this factor (not the named configuration any more): "
                          "with transition costs far above the spread of the layer costs nothing can be pruned, "
@@ -249,6 +252,10 @@ def run_config(cfg, args, torch, binding, workloads):
     if args.r_scale != 1:
         w.R = w.R * args.r_scale
         w.name += f" with R x {args.r_scale}"
+    if args.c_scale != 1:
+        w.R = w.R * args.c_scale
+        w.c = w.c * args.c_scale
+        w.name += f" with c and R x {args.c_scale}"
     base_flags = ((binding.GALV_DP_FORCE_INT64 if args.force_int64 else 0) |
                   (binding.GALV_DP_NO_U32 if args.no_u32 else 0) |
                   (binding.GALV_DP_BP_U8 if args.bp_u8 else 0))
@@ -369,7 +376,7 @@ def run_config(cfg, args, torch, binding, workloads):
                         "of a tile are pruned; alu.candidates_evaluated_share, from galv_dp_get_stats)",
                 "single_stream": single, "alu": alu_obj, "hbm": hbm_obj}
 
-    kinds = {3: "u32", 0: "f64", 2: "f64", 1: "int64"}
+    kinds = {3: "u32", 4: "u32", 0: "f64", 2: "f64", 1: "int64"}
     used = sorted({kinds[int(st)] for st in status if int(st) in kinds})
     dtype = ("+".join(used) or "none") + " (exact integer keys; int64 costs in, int64 costs out)"
 
@@ -395,6 +402,7 @@ def run_config(cfg, args, torch, binding, workloads):
         "cost_rows_fetched_share": fetched_share,
         "solve_ms_median": solve_ms[len(solve_ms) // 2],
         "instances_by_path": {"u32_keys": int((status == binding.GALV_INSTANCE_OK_FAST_U32).sum()),
+                              "u32_keys_64bit_cells": int((status == binding.GALV_INSTANCE_OK_U32_WIDE).sum()),
                               "f64_keys_32bit_cells": int((status == binding.GALV_INSTANCE_OK_FAST).sum()),
                               "f64_keys_64bit_cells": int((status == binding.GALV_INSTANCE_OK_FAST_WIDE).sum()),
                               "int64": int((status == binding.GALV_INSTANCE_OK_INT64).sum())},

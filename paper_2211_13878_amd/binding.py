@@ -33,6 +33,7 @@ def GALV_DP_STREAMS(n: int) -> int:
     return int(n) << 8
 
 GALV_INSTANCE_OK_FAST, GALV_INSTANCE_OK_INT64, GALV_INSTANCE_OK_FAST_WIDE, GALV_INSTANCE_OK_FAST_U32 = 0, 1, 2, 3
+GALV_INSTANCE_OK_U32_WIDE = 4
 GALV_INSTANCE_BAD_VALUE = -1
 
 EXPORTS = ("galv_dp_workspace_bytes", "galv_dp_create", "galv_dp_solve_batched",

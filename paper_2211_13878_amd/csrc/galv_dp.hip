@@ -133,7 +133,7 @@ struct Layout {
     uint32_t *dclamp;     // 32-bit-key path: largest R + 1, the clamp of relative costs  [B]
     int32_t *status;      // per instance        [B]
     int32_t *last;        // best last strategy  [B]
-    int32_t *lead_mode;   // whose infinity leads the rows hold: 1 narrow, 2 wide, 0 none  [B]
+    int32_t *lead_mode;   // whose infinity leads the rows hold (lead_kind), 0 none  [B]
     uint32_t *stats;      // 32-bit-key sweeps, per tile: rows reduced << 16 | rows listed; rows fetched  [B][L-1][n_tiles][2]
     const int64_t *c;
     const int32_t *m;
@@ -143,6 +143,15 @@ struct Layout {
 };
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
+// Lane `lane`'s value of v, as a wave-uniform scalar.
+__device__ __forceinline__ uint32_t read_lane(uint32_t v, int lane) {
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, lane);
+}
+__device__ __forceinline__ uint64_t read_lane(uint64_t v, int lane) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, lane);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), lane);
+    return (uint64_t)hi << 32 | lo;
+}
 
 // Read-only view through the constant address space: data that no thread writes
 // while the kernel runs (inputs, tables packed by the preparation kernel).  With a
@@ -157,6 +166,14 @@ __device__ __forceinline__ ConstPtr<T> as_const(const T *p) {
 // Storage of the cost rows: 32-bit cells for both packed-key paths of small costs.
 __device__ __forceinline__ bool narrow_cells(int st) {
     return st == GALV_INSTANCE_OK_FAST || st == GALV_INSTANCE_OK_FAST_U32;
+}
+// What the infinity lead in front of a cost row must hold: 1 uint32 2^31, 2 double +inf,
+// 3 uint64 2^62, 0 no lead is read.
+__device__ __forceinline__ int lead_kind(int st) {
+    if (narrow_cells(st)) return 1;
+    if (st == GALV_INSTANCE_OK_FAST_WIDE) return 2;
+    if (st == GALV_INSTANCE_OK_U32_WIDE) return 3;
+    return 0;
 }
 
 // Back-pointer of un-shifted cell idx, whichever width the handle stores.
@@ -253,7 +270,7 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
     if (tid == 0) bad = 0;
     __syncthreads();
 
-    const int budget = a.budget[b];
+    const int budget = uniform(a.budget[b]);
     if (tid == 0 && (budget < 0 || budget > a.E_max)) bad = 1;
 
     // sum over layers of max_s c(l,s), saturating at 2^62
@@ -333,6 +350,12 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
                              ((2 * rmax_all + 2) << a.k_bits) <= (1ull << 32);
             st = u32 ? GALV_INSTANCE_OK_FAST_U32 : GALV_INSTANCE_OK_FAST;
             a.dclamp[b] = (uint32_t)(rmax_all + 1);
+        } else if (a.synth_l1 && !(flags & GALV_DP_NO_U32) &&
+                   ((2 * rmax_all + 2) << a.k_bits) <= (1ull << 32)) {
+            // costs need 64-bit cells, but only RELATIVE costs (clamped at R_max + 1) enter the keys:
+            // the 32-bit-key arithmetic and its pruning apply all the same (row-sharing variants)
+            st = GALV_INSTANCE_OK_U32_WIDE;
+            a.dclamp[b] = (uint32_t)(rmax_all + 1);
         } else if (bound + 1 <= (1ull << (52 - a.k_bits))) {
             st = GALV_INSTANCE_OK_FAST_WIDE;    // keys fit the 52-bit mantissa
         } else {
@@ -343,13 +366,13 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
     }
     __syncthreads();
     const int st = status_s;
-    if (!narrow_cells(st) && st != GALV_INSTANCE_OK_FAST_WIDE) return;
+    if (!narrow_cells(st) && st != GALV_INSTANCE_OK_FAST_WIDE && st != GALV_INSTANCE_OK_U32_WIDE) return;
 
     // R key = R * 2^k + s' (s' = row = former strategy); padded columns are +inf so
     // that they never win and never read past the caller's matrix.
     const double scale = (double)(1ull << a.k_bits);
     double *Rk = a.Rk + (int64_t)b * nR * S * a.S_pad;
-    if (st == GALV_INSTANCE_OK_FAST_U32) {
+    if (st == GALV_INSTANCE_OK_FAST_U32 || st == GALV_INSTANCE_OK_U32_WIDE) {
         // 32-bit keys in the first half of each matrix's slot: rows of S_pad words, one matrix
         // every S * S_pad doubles; padded columns hold the largest word.
         for (int64_t i = tid; i < nR * S * a.S_pad; i += kThreads) {
@@ -368,13 +391,13 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
             Rk[i] = (s < S) ? (double)R[(k * S + sp) * S + s] * scale + (double)sp : INFINITY;
         }
     }
-    // c(l,s) in the form the epilogue adds: the integer itself (narrow) or the
-    // double c * 2^k (wide).
+    // c(l,s) in the form the epilogue adds: the integer itself (integer cells) or the
+    // double c * 2^k (cells that hold 64-bit keys).
     uint64_t *ck = a.ck + (int64_t)b * L * a.S_pad;
     for (int64_t i = tid; i < L * a.S_pad; i += kThreads) {
         const int64_t s = i % a.S_pad, l = i / a.S_pad;
         const int64_t v = (s < S) ? c[l * S + s] : 0;
-        ck[i] = narrow_cells(st)
+        ck[i] = (narrow_cells(st) || st == GALV_INSTANCE_OK_U32_WIDE)
                     ? (uint64_t)v
                     : (uint64_t)__double_as_longlong((double)v * scale);
     }
@@ -406,7 +429,7 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
 // final_kernel records the mode once the solve is through.
 __global__ __launch_bounds__(kThreads) void init_kernel(Layout a, int fresh) {
     const int b = blockIdx.z, s = blockIdx.y;
-    const int st = a.status[b];
+    const int st = uniform(a.status[b]);
     if (st < 0) return;
     const int64_t base = ((int64_t)b * a.S_pad + s) * a.row * 8;
     const int64_t x0 = (int64_t)blockIdx.x * kThreads + threadIdx.x, step = (int64_t)gridDim.x * kThreads;
@@ -415,8 +438,9 @@ __global__ __launch_bounds__(kThreads) void init_kernel(Layout a, int fresh) {
         for (int64_t x = a.lead + x0; x < a.row; x += step) reinterpret_cast<int64_t *>(a.U[0] + base)[x] = c0;
         return;
     }
-    const bool leads = fresh || a.lead_mode[b] != (narrow_cells(st) ? 1 : 2);
-    const bool row0 = !(st == GALV_INSTANCE_OK_FAST_U32 && a.synth_l1 && a.L > 1);
+    const bool leads = fresh || a.lead_mode[b] != lead_kind(st);
+    const bool u32_keys = st == GALV_INSTANCE_OK_FAST_U32 || st == GALV_INSTANCE_OK_U32_WIDE;
+    const bool row0 = !(u32_keys && a.synth_l1 && a.L > 1);
     if (!leads && !row0) return;                   // the usual case after a handle's first solve
     const uint64_t cs = a.ck[((int64_t)b * a.L) * a.S_pad + s];
     if (narrow_cells(st)) {
@@ -429,6 +453,16 @@ __global__ __launch_bounds__(kThreads) void init_kernel(Layout a, int fresh) {
             }
         if (row0)
             for (int64_t x = a.lead + x0; x < a.row; x += step) u0[x] = Narrow::first_layer(cs);
+    } else if (st == GALV_INSTANCE_OK_U32_WIDE) {
+        uint64_t *u0 = reinterpret_cast<uint64_t *>(a.U[0] + base);
+        uint64_t *u1 = reinterpret_cast<uint64_t *>(a.U[1] + base);
+        if (leads)
+            for (int64_t x = x0; x < a.lead; x += step) {
+                u0[x] = (uint64_t)kInf;
+                u1[x] = (uint64_t)kInf;
+            }
+        if (row0)
+            for (int64_t x = a.lead + x0; x < a.row; x += step) u0[x] = cs;
     } else {
         double *u0 = reinterpret_cast<double *>(a.U[0] + base);
         double *u1 = reinterpret_cast<double *>(a.U[1] + base);
@@ -975,9 +1009,15 @@ constexpr int keep_rows(int cap) { return cap <= 64 ? 16 : 32; }
 //      rows, read again through the caches and turned into keys on the fly.
 // Only the survivors' keys live in LDS (keep_rows rows instead of S), which is what lets four
 // 8-wave workgroups share a CU at S = 128.
-template <int TS, int TE, int NG, class BP>
+template <int TS, int TE, int NG, class BP, class Cell>
 __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, int budget,
-                                                 int64_t tile_start) {
+                                                 int64_t tile_start, bool add_stats) {
+    // Cell: uint32_t (costs below 2^31, infinity = 2^31) or uint64_t (any cost up to the 2^62
+    // precondition, infinity = 2^62).  Only RELATIVE costs enter the 32-bit keys, so the wide form
+    // runs the same arithmetic and the same pruning; it moves 8-byte cells.
+    constexpr bool kWide = sizeof(Cell) == 8;
+    constexpr Cell kInfCell = kWide ? (Cell)kInf : (Cell)kInf32;
+    constexpr Cell kAllOnes = ~(Cell)0;
     static_assert(TS <= 16, "one scalar load fetches the R keys of a row");
     constexpr int kCols = kWave * TE;
     constexpr int kKeep = keep_rows(TS * NG);
@@ -989,10 +1029,10 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
 
     const int64_t S = a.S;
     const int k = a.k_bits;
-    const int64_t pitch = a.row * 2;               // 32-bit cells between the rows of two strategies
-    const uint32_t *Up = reinterpret_cast<const uint32_t *>(a.U[(l - 1) & 1]) +
-                         (int64_t)b * a.S_pad * pitch + a.lead + tile_start;
-    uint32_t *Un = reinterpret_cast<uint32_t *>(a.U[l & 1]) + ((int64_t)b * a.S_pad + s0) * pitch +
+    const int64_t pitch = a.row * (8 / (int64_t)sizeof(Cell));   // cells between the rows of two strategies
+    const Cell *Up = reinterpret_cast<const Cell *>(a.U[(l - 1) & 1]) +
+                     (int64_t)b * a.S_pad * pitch + a.lead + tile_start;
+    Cell *Un = reinterpret_cast<Cell *>(a.U[l & 1]) + ((int64_t)b * a.S_pad + s0) * pitch +
                    a.lead + e0;
     BP *bp = static_cast<BP *>(a.bp) + (((int64_t)b * (a.L - 1) + (l - 1)) * S + s0) * a.e_pad + e0;
     const int r_sel = a.r_idx ? a.r_idx[(int64_t)b * a.L + l] : 0;
@@ -1009,21 +1049,22 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
     // made up here (infinity below the shift) instead of being read.
     const bool first = l == 1;                     // uniform
     const ConstPtr<uint64_t> ck0 = as_const(a.ck + (int64_t)b * a.L * a.S_pad);
-    auto load_row = [&](uint64_t ent, uint32_t (&out)[TE]) {
+    auto load_row = [&](uint64_t ent, Cell (&out)[TE]) {
         const uint32_t sp = (uint32_t)ent, shift = (uint32_t)(ent >> 32);
         if (first) {
-            const uint32_t c0 = (uint32_t)ck0[sp];
+            const Cell c0 = (Cell)ck0[sp];
 #pragma unroll
-            for (int j = 0; j < TE; ++j) out[j] = e0 + j * kWave >= (int64_t)shift ? c0 : kInf32;
+            for (int j = 0; j < TE; ++j) out[j] = e0 + j * kWave >= (int64_t)shift ? c0 : kInfCell;
         } else {
-            const uint32_t *p = Up + (int64_t)sp * pitch - (int64_t)shift;
+            const Cell *p = Up + (int64_t)sp * pitch - (int64_t)shift;
 #pragma unroll
             for (int j = 0; j < TE; ++j) out[j] = p[(uint32_t)lane + j * kWave];
         }
     };
 
-    uint32_t *part = lds_cells;                    // [NG][kCols] partial column minima
-    uint32_t *count = part + NG * kCols;           // surviving rows (4 words reserved)
+    Cell *part = reinterpret_cast<Cell *>(lds_cells);               // [NG][kCols] partial column minima
+    Cell *wave_min = part + NG * kCols;                             // [NG] the waves' minima of the peek
+    uint32_t *count = reinterpret_cast<uint32_t *>(wave_min + NG);  // [0] surviving rows, [2] rows fetched
     uint32_t *meta = count + 4;                    // [kKeep] strategy index of a kept row
     uint32_t *keys = meta + kKeep;                 // [kKeep][kCols] its keys
 
@@ -1032,9 +1073,9 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
     for (int s = 0; s < TS; ++s)
 #pragma unroll
         for (int j = 0; j < TE; ++j) acc[s][j] = 0xffffffffu;
-    uint32_t cmin[TE];
+    Cell cmin[TE];
 #pragma unroll
-    for (int j = 0; j < TE; ++j) cmin[j] = 0xffffffffu;
+    for (int j = 0; j < TE; ++j) cmin[j] = kAllOnes;
 
     if (g == 0 && lane == 0) count[0] = 0;
 
@@ -1061,49 +1102,48 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
         // One gather for the whole wave: lane r (r < TS) fetches row r's cell in the column before
         // the tile (for the first tile that is the infinity lead), lane 32 + r its cell in the last column.  The rows' addresses are wave-uniform
         // scalars; each lane picks its own with a chain of selects.
-        uint32_t last_c[TS];
-        uint32_t first_min = 0xffffffffu;
+        Cell last_c[TS];
+        Cell first_min = kAllOnes;
         static_assert(TS <= 32, "one lane per row and boundary");
         const int my_row = lane & 31;
         const bool my_last = lane >= 32;
-        const uint32_t *my_p = Up;                 // any valid address for the idle lanes
-        uint32_t my_c0 = 0;
+        const Cell *my_p = Up;                     // any valid address for the idle lanes
+        Cell my_c0 = 0;
         bool my_below = false;                     // (first layer) this lane's column lies below the row's shift
 #pragma unroll
         for (int r = 0; r < TS; ++r) {
             const uint64_t ent = vl[g + NG * r];
             const uint32_t sp = (uint32_t)ent, shift = (uint32_t)(ent >> 32);
             if (first) {
-                const uint32_t c0 = (uint32_t)ck0[sp];
+                const Cell c0 = (Cell)ck0[sp];
                 if (my_row == r) {
                     my_c0 = c0;
                     my_below = tile_start + (my_last ? kCols - 1 : -1) < (int64_t)shift;
                 }
             } else {
-                const uint32_t *p = Up + (int64_t)sp * pitch - (int64_t)shift;
+                const Cell *p = Up + (int64_t)sp * pitch - (int64_t)shift;
                 if (my_row == r) my_p = p;
             }
         }
-        uint32_t mine;
+        Cell mine;
         if (first)
-            mine = my_below ? kInf32 : my_c0;
+            mine = my_below ? kInfCell : my_c0;
         else
             mine = my_p[my_last ? kCols - 1 : -1];
 #pragma unroll
         for (int r = 0; r < TS; ++r) {
-            first_min = min(first_min, (uint32_t)__builtin_amdgcn_readlane((int)mine, r));
-            last_c[r] = (uint32_t)__builtin_amdgcn_readlane((int)mine, 32 + r);
+            first_min = min(first_min, read_lane(mine, r));
+            last_c[r] = read_lane(mine, 32 + r);
         }
-        uint32_t *peek = count + 2;                // [0]: rows read, then behind the list: the waves' minima
-        uint32_t *wave_min = keys + kKeep * kCols; // [NG]
+        uint32_t *peek = count + 2;                // rows fetched by the workgroup
         if (lane == 0) wave_min[g] = first_min;
         if (g == 0 && lane == 0) peek[0] = 0;
         __syncthreads();
-        uint32_t cmin_first = 0xffffffffu;
+        Cell cmin_first = kAllOnes;
 #pragma unroll
-        for (int w = 0; w < NG; ++w) cmin_first = min(cmin_first, (uint32_t)uniform((int)wave_min[w]));
-        // an unreachable first column (Cmin_first = infinity) bounds nothing: read every row
-        const uint32_t limit = cmin_first < kInf32 ? cmin_first + dmax : 0xffffffffu;
+        for (int w = 0; w < NG; ++w) cmin_first = min(cmin_first, read_lane(wave_min[w], 0));
+        // an unreachable column before the tile (Cmin_before = infinity) bounds nothing: read every row
+        const Cell limit = cmin_first < kInfCell ? cmin_first + (Cell)dmax : kAllOnes;
         int mine_read = 0;
 #pragma unroll
         for (int r = 0; r < TS; ++r)
@@ -1114,18 +1154,18 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
         if (lane == 0 && mine_read) atomicAdd(&peek[0], (uint32_t)mine_read);
     }
 
-    uint32_t rowc[TS][TE];
+    Cell rowc[TS][TE];
     if (n > 0) {                                   // workgroup-uniform
-        uint32_t pm[TE];
+        Cell pm[TE];
 #pragma unroll
-        for (int j = 0; j < TE; ++j) pm[j] = 0xffffffffu;
+        for (int j = 0; j < TE; ++j) pm[j] = kAllOnes;
 #pragma unroll
         for (int r = 0; r < TS; ++r) {
             if (keep >> r & 1) {
                 load_row(vl[g + NG * r], rowc[r]);
             } else {
 #pragma unroll
-                for (int j = 0; j < TE; ++j) rowc[r][j] = 0xffffffffu;       // leaves every minimum alone
+                for (int j = 0; j < TE; ++j) rowc[r][j] = kAllOnes;          // leaves every minimum alone
             }
         }
 #pragma unroll
@@ -1145,12 +1185,13 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
         for (int r = 0; r < TS; ++r) {
             const int i = g + NG * r;
             if (keep >> r & 1) {                   // listed (the padding repeats a listed row) and read
-                uint32_t d[TE];
+                uint32_t d[TE];                    // relative cost, clamped: all that a key needs
                 bool live = false;
 #pragma unroll
                 for (int j = 0; j < TE; ++j) {
-                    d[j] = rowc[r][j] - cmin[j];
-                    live |= d[j] < dmax && cmin[j] < kInf32;
+                    const Cell rel = rowc[r][j] - cmin[j];
+                    d[j] = (uint32_t)min(rel, (Cell)dmax);
+                    live |= rel < (Cell)dmax && cmin[j] < kInfCell;
                 }
                 if (__builtin_amdgcn_ballot_w64(live) != 0) {        // wave-uniform
                     uint32_t slot = 0;
@@ -1159,7 +1200,7 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
                     if (slot < (uint32_t)kKeep) {
 #pragma unroll
                         for (int j = 0; j < TE; ++j)
-                            keys[slot * kCols + j * kWave + lane] = min(d[j], dmax) << k;
+                            keys[slot * kCols + j * kWave + lane] = d[j] << k;
                         if (lane == 0) meta[slot] = (uint32_t)vl[i];
                     }
                 }
@@ -1173,14 +1214,16 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
     if (g == 0 && lane == 0) {                     // statistics: how much the pruning removed
         uint32_t *st = a.stats + 2 * (((int64_t)b * (a.L - 1) + (l - 1)) * a.n_tiles +
                                       (uint32_t)tile_start / (uint32_t)a.tile_e);
-        st[0] = (uint32_t)(nsurv <= kKeep ? nsurv : n) << 16 | (uint32_t)n;
-        st[1] = n > 0 ? count[2] : 0u;             // rows fetched
+        const uint32_t rows = (uint32_t)(nsurv <= kKeep ? nsurv : n) << 16 | (uint32_t)n;
+        const uint32_t fetched = n > 0 ? count[2] : 0u;
+        st[0] = add_stats ? st[0] + rows : rows;   // (a tile swept in several parts adds them up)
+        st[1] = add_stats ? st[1] + fetched : fetched;
     }
     if (nsurv > 0) {
         const bool pruned = nsurv <= kKeep;        // workgroup-uniform
         const int nrow = pruned ? nsurv : n;
         const int npair = (nrow + 1) / 2;          // an odd tail repeats its entry: min(x, x) = x
-        uint32_t va[2][TE], vb[2][TE];
+        Cell va[2][TE], vb[2][TE];
         int spa[2], spb[2];
         R32Row<TS> ra[2], rb[2];
         auto request = [&](int q, int pr) {
@@ -1196,23 +1239,23 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
                 }
             } else {
                 const uint64_t ea = vl[ia], eb = vl[ib];
-                spa[q] = (int)(uint32_t)ea;
-                spb[q] = (int)(uint32_t)eb;
+                spa[q] = uniform((int)(uint32_t)ea);     // (scalars already; said so for the compiler, which
+                spb[q] = uniform((int)(uint32_t)eb);     // merges them with the other branch's values)
                 load_row(ea, va[q]);
                 load_row(eb, vb[q]);
             }
         };
         auto reduce_pair = [&](int q) {
             // keys of the next pair's rows, in flight under this pair's arithmetic
-            ra[q ^ 1].request(Rk + (int64_t)spa[q ^ 1] * a.S_pad);
-            rb[q ^ 1].request(Rk + (int64_t)spb[q ^ 1] * a.S_pad);
+            ra[q ^ 1].request(Rk + (int64_t)uniform(spa[q ^ 1]) * a.S_pad);
+            rb[q ^ 1].request(Rk + (int64_t)uniform(spb[q ^ 1]) * a.S_pad);
             uint32_t da[TE], db[TE];
 #pragma unroll
             for (int j = 0; j < TE; ++j) {         // kept rows are keys already; others are raw cells
-                const uint32_t ka = min(va[q][j] - cmin[j], dmax) << k;
-                const uint32_t kb = min(vb[q][j] - cmin[j], dmax) << k;
-                da[j] = pruned ? va[q][j] : ka;
-                db[j] = pruned ? vb[q][j] : kb;
+                const uint32_t ka = (uint32_t)min((Cell)(va[q][j] - cmin[j]), (Cell)dmax) << k;
+                const uint32_t kb = (uint32_t)min((Cell)(vb[q][j] - cmin[j]), (Cell)dmax) << k;
+                da[j] = pruned ? (uint32_t)va[q][j] : ka;
+                db[j] = pruned ? (uint32_t)vb[q][j] : kb;
             }
 #pragma unroll
             for (int s = 0; s < TS; ++s)
@@ -1221,8 +1264,8 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
         };
         request(0, 0);
         request(1, 1);
-        ra[0].request(Rk + (int64_t)spa[0] * a.S_pad);
-        rb[0].request(Rk + (int64_t)spb[0] * a.S_pad);
+        ra[0].request(Rk + (int64_t)uniform(spa[0]) * a.S_pad);
+        rb[0].request(Rk + (int64_t)uniform(spb[0]) * a.S_pad);
         r32_await(ra[0], rb[0]);
         int pr = 0;
         for (; pr + 2 <= npair; pr += 2) {
@@ -1238,12 +1281,12 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
 #pragma unroll
     for (int s = 0; s < TS; ++s) {
         if (s0 + s < S) {
-            const uint32_t cs = (uint32_t)ck[s];
+            const Cell cs = (Cell)ck[s];
 #pragma unroll
             for (int j = 0; j < TE; ++j) {
-                const bool alive = cmin[j] < kInf32;
+                const bool alive = cmin[j] < kInfCell;
                 const uint32_t key = acc[s][j];
-                Un[(int64_t)s * pitch + j * kWave] = alive ? cmin[j] + (key >> k) + cs : kInf32;
+                Un[(int64_t)s * pitch + j * kWave] = alive ? cmin[j] + (Cell)(key >> k) + cs : kInfCell;
                 __builtin_nontemporal_store((BP)(alive ? (int32_t)(key & mask) : -1),
                                             &bp[(int64_t)s * a.e_pad + j * kWave]);
             }
@@ -1256,9 +1299,10 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
 template <int TS, int TE, int NG, int WPE, class BP, int W, int UX, int SHARE>
 __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) {
     const int b = a.b_off + blockIdx.z * a.b_step;
-    const int st = a.status[b];
+    // (one value per workgroup; said so, so that nothing derived from them counts as divergent)
+    const int st = uniform(a.status[b]);
     if (st < 0) return;
-    const int budget = a.budget[b];
+    const int budget = uniform(a.budget[b]);
 #if GALV_XCD_MAP
     // Workgroups go round-robin to the 8 XCDs in the order of their linear index, and grid.x is
     // a multiple of 8, so blockIdx.x & 7 names the XCD.  Each XCD takes a contiguous eighth of
@@ -1274,9 +1318,19 @@ __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) 
     if (tile_start > budget) return;
     if (st == GALV_INSTANCE_OK_FAST_U32) {
         if constexpr (SHARE)
-            sweep_u32_shared<TS, TE * UX, NG, BP>(a, l, b, budget, tile_start);
+            sweep_u32_shared<TS, TE * UX, NG, BP, uint32_t>(a, l, b, budget, tile_start, false);
         else
             sweep_u32<TS, TE * UX, NG, BP>(a, l, b, budget, tile_start);
+    } else if (st == GALV_INSTANCE_OK_U32_WIDE) {
+        // 8-byte cells: 64 columns at a time keep the rows within the registers the narrow form uses
+        // (the preparation kernel grants this path to row-sharing variants only)
+        if constexpr (SHARE) {
+            for (int h = 0; h < TE * UX; ++h) {
+                if (tile_start + h * kWave > budget) break;          // workgroup-uniform
+                if (h) __syncthreads();                              // the LDS of the part before is free again
+                sweep_u32_shared<TS, 1, NG, BP, uint64_t>(a, l, b, budget, tile_start + h * kWave, h > 0);
+            }
+        }
     } else if (st == GALV_INSTANCE_OK_FAST) {
         for (int h = 0; h < UX; ++h)
             sweep_fast<TS, TE, NG, Narrow, BP>(a, l, b, budget, tile_start + h * (a.tile_e / UX));
@@ -1301,6 +1355,10 @@ __device__ __forceinline__ int64_t last_layer_cost(const Layout &a, int b, int s
         return Narrow::to_int64(reinterpret_cast<const uint32_t *>(U)[x], a.k_bits);
     if (st == GALV_INSTANCE_OK_FAST_WIDE)
         return Wide::to_int64(reinterpret_cast<const double *>(U)[x], a.k_bits);
+    if (st == GALV_INSTANCE_OK_U32_WIDE) {
+        const uint64_t v = reinterpret_cast<const uint64_t *>(U)[x];
+        return v >= (uint64_t)kInf ? kInf : (int64_t)v;
+    }
     return reinterpret_cast<const int64_t *>(U)[x];
 }
 
@@ -1308,10 +1366,10 @@ __device__ __forceinline__ int64_t last_layer_cost(const Layout &a, int b, int s
 __global__ __launch_bounds__(kThreads) void final_kernel(Layout a, int64_t *best_cost,
                                                          int32_t *best_last) {
     const int b = blockIdx.x;
-    const int st = a.status[b];
+    const int st = uniform(a.status[b]);
     __shared__ int64_t val[kMaxS];
     if (st >= 0) {
-        const int budget = a.budget[b];
+        const int budget = uniform(a.budget[b]);
         for (int s = threadIdx.x; s < a.S; s += kThreads) val[s] = last_layer_cost(a, b, st, budget, s);
     }
     __syncthreads();
@@ -1328,7 +1386,7 @@ __global__ __launch_bounds__(kThreads) void final_kernel(Layout a, int64_t *best
         best_last[b] = last;
         a.last[b] = last;
         // every block of init_kernel has long finished: safe to record what the leads hold
-        a.lead_mode[b] = st < 0 || st == GALV_INSTANCE_OK_INT64 ? 0 : (narrow_cells(st) ? 1 : 2);
+        a.lead_mode[b] = st < 0 ? 0 : lead_kind(st);
     }
 }
 
@@ -1363,7 +1421,7 @@ __global__ __launch_bounds__(kThreads) void stats_kernel(Layout a, int64_t *out)
     const int b = blockIdx.x;
     __shared__ unsigned long long red[3][kThreads];
     unsigned long long done = 0, listed = 0, fetched = 0;
-    if (a.status[b] == GALV_INSTANCE_OK_FAST_U32) {
+    if (a.status[b] == GALV_INSTANCE_OK_FAST_U32 || a.status[b] == GALV_INSTANCE_OK_U32_WIDE) {
         const int nt = a.budget[b] / a.tile_e + 1;
         for (int64_t i = threadIdx.x; i < (int64_t)(a.L - 1) * nt; i += kThreads) {
             const uint32_t *v = a.stats + 2 * (((int64_t)b * (a.L - 1) + i / nt) * a.n_tiles + i % nt);
@@ -1443,7 +1501,7 @@ __global__ __launch_bounds__(kThreads) void best_per_budget_kernel(Layout a, int
     const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (e > a.E_max) return;
     const int b = blockIdx.y;
-    const int st = a.status[b];
+    const int st = uniform(a.status[b]);
     int64_t opt = kInf;
     int32_t last = -1;
     if (st >= 0 && e <= a.budget[b]) best_at(a, b, st, e, opt, last);
@@ -1462,7 +1520,7 @@ __global__ __launch_bounds__(kWave) void backtrack_queries_kernel(Layout a, int 
     int64_t opt = kInf;
     int32_t last = -1;
     if (b >= 0 && b < a.B) {
-        const int st = a.status[b];
+        const int st = uniform(a.status[b]);
         if (st >= 0 && e >= 0 && e <= a.budget[b]) best_at(a, b, st, e, opt, last);
     }
     if (cost) cost[q] = opt;
@@ -1476,8 +1534,8 @@ __global__ __launch_bounds__(kThreads) void export_kernel(Layout a, int b, int64
     const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (e > a.E_max) return;
     const int l = blockIdx.y;
-    const int st = a.status[b];
-    const int budget = a.budget[b];
+    const int st = uniform(a.status[b]);
+    const int budget = uniform(a.budget[b]);
     const bool live = st >= 0 && e <= budget;
     if (l == a.L) {
         for (int s = 0; s < a.S; ++s)
@@ -1757,7 +1815,10 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     p->lds_bytes = 0;
     if (v.share) {
         const size_t cols = (size_t)kWave * v.te * v.ux, keep = keep_rows(v.ts * v.ng);
-        p->lds_bytes = (unsigned)(((size_t)v.ng * cols + 4 + keep + keep * cols + v.ng) * sizeof(uint32_t));
+        const size_t narrow = ((size_t)v.ng * cols + v.ng + 4 + keep + keep * cols) * sizeof(uint32_t);
+        // the 8-byte-cell form works on 64 columns at a time
+        const size_t wide = ((size_t)v.ng * kWave + v.ng) * sizeof(uint64_t) + (4 + keep + keep * kWave) * sizeof(uint32_t);
+        p->lds_bytes = (unsigned)(narrow > wide ? narrow : wide);
     }
     if (p->lds_bytes > 160u * 1024u)
         return fail(GALV_ERR_RANGE, "internal: staging variant needs %u bytes of LDS", p->lds_bytes);

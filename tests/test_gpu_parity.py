@@ -362,6 +362,39 @@ def test_mid_range_values_take_wide_storage():
     assert (cost[cost < INF] > (1 << 31)).any()
 
 
+@pytest.mark.parametrize("S", [5, 22, 44, 100, 128, 200])
+def test_large_costs_with_small_transition_costs_keep_32bit_keys(S):
+    """Costs around 2^40 need 64-bit cells, but the keys hold only RELATIVE costs (clamped at the
+    largest R + 1): with small transition costs the library keeps the 32-bit-key arithmetic and
+    its pruning over 8-byte cells.  One instance keeps small costs (the choice is per instance);
+    GALV_DP_NO_U32 sends the large ones to the 64-bit-key kernels instead."""
+    w = workloads.random_workload(600 + S, 4, 6, S, 700, nR=2, m_range=(0, 150), c_range=(0, 1 << 40),
+                                  r_range=(0, 3000), infeasible=0.08, zero_diagonal=False)
+    w.c[3] = w.c[3] % 100000
+    w.budget[:] = [700, 641, 577, 692]
+    for peek in (binding.GALV_DP_FORCE_PEEK, binding.GALV_DP_NO_PEEK):
+        cost, _, _, status = check_against_oracle(w, flags=peek, table_instances=[0, 1, 3])
+        assert list(status) == [binding.GALV_INSTANCE_OK_U32_WIDE] * 3 + [binding.GALV_INSTANCE_OK_FAST_U32]
+        assert (cost[cost < INF] > (1 << 33)).any()
+    _, _, _, status = check_against_oracle(w, flags=binding.GALV_DP_NO_U32, table_instances=[1])
+    assert list(status) == [binding.GALV_INSTANCE_OK_FAST_WIDE] * 3 + [binding.GALV_INSTANCE_OK_FAST]
+    check_against_oracle(w, flags=binding.GALV_DP_BP_U8 | binding.GALV_DP_STREAMS(2), table_instances=[2])
+
+
+def test_wide_integer_keys_when_nothing_can_be_pruned_and_at_the_cost_limit():
+    """Same path with transition costs above the cost spread (the kept-row list overflows: full
+    loop over 8-byte cells) and with costs close to the 2^62 precondition."""
+    w = workloads.random_workload(77, 3, 5, 44, 500, nR=2, m_range=(0, 120), c_range=(1 << 36, (1 << 36) + 9),
+                                  r_range=(1000, 5000), infeasible=0.05, zero_diagonal=False)
+    w.budget[0] = 500
+    _, _, _, status = check_against_oracle(w, flags=binding.GALV_DP_FORCE_PEEK, table_instances=[0, 1, 2])
+    assert (status == binding.GALV_INSTANCE_OK_U32_WIDE).all()
+    w = workloads.random_workload(78, 2, 4, 9, 300, m_range=(0, 90), c_range=(0, (1 << 59) - 1), r_range=(0, 99))
+    w.budget[0] = 300
+    cost, _, _, status = check_against_oracle(w, table_instances=[0, 1])
+    assert (status == binding.GALV_INSTANCE_OK_U32_WIDE).all() and (cost[cost < INF] > (1 << 58)).any()
+
+
 def test_path_limits_by_transition_cost():
     """32-bit integer keys need (2 * largest R + 2) * 2^k <= 2^32.  With k = 4: R up to 2^27 - 1 just
     fits; one more and the instance takes 64-bit keys (costs still fit 32-bit cells).  Clamping of
