@@ -104,8 +104,9 @@ typedef struct {
 #define GALV_INSTANCE_OK_FAST_U32 3   /* as OK_FAST and, besides, (2 * largest R + 2) * 2^k <= 2^32
                                         (k = index bits): keys of relative costs in 32-bit
                                         integers, three instructions per two candidates      */
-#define GALV_INSTANCE_OK_U32_WIDE 4   /* costs too large for 32-bit cells but (2 * largest R + 2) * 2^k <= 2^32:
-                                        the same 32-bit keys of relative costs, over 64-bit cells    */
+#define GALV_INSTANCE_OK_U32_WIDE 4   /* plan costs beyond 32-bit cells, but (2 * largest R + 2) * 2^k <= 2^32
+                                        and n_strategies <= 256: the same 32-bit keys of relative
+                                        costs (their width depends on R only), over 64-bit cells  */
 #define GALV_INSTANCE_BAD_VALUE (-1) /* a value violates the preconditions above            */
 
 /*

@@ -29,6 +29,8 @@
 //    a tile is left out of the inner loop, and (rows being non-increasing along the budget
 //    axis) two of its cells tell whether it needs to be fetched at all.  With the usual spread
 //    of layer costs some 90-95 % of the candidates fall away and the sweep is bound by HBM.
+//    The keys' width depends on the transition costs only; when the costs themselves outgrow
+//    32-bit cells, the same body runs over 64-bit cells (up to 256 strategies).
 //  * 64-bit keys: key = cost * 2^k + s' (k = ceil(log2 S)) lives in the mantissa of a double
 //    whose exponent is pinned, K = 2^52 + key; one v_add_f64 + one v_min_f64 per candidate,
 //    exact while K stays below 2^53.  Two storage widths: narrow (costs below 2^31 stored as
@@ -143,6 +145,10 @@ struct Layout {
 };
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
+// Position of the thread, without the thread-index register: the kernel reads that register
+// once, at its top (wave number, a scalar), and the lane number is recomputed where it is
+// needed, so no vector register stays occupied from the kernel's entry to the body it selects.
+__device__ __forceinline__ int lane_id() { return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)); }
 // Lane `lane`'s value of v, as a wave-uniform scalar.
 __device__ __forceinline__ uint32_t read_lane(uint32_t v, int lane) {
     return (uint32_t)__builtin_amdgcn_readlane((int)v, lane);
@@ -480,7 +486,7 @@ __global__ __launch_bounds__(kThreads) void init_kernel(Layout a, int fresh) {
 // General 64-bit integer body: one budget column per thread at a time, strategy
 // columns in chunks of CH running (min, argmin) pairs.
 template <int CH>
-__device__ __forceinline__ void sweep_int64(const Layout &a, int l, int b, int budget,
+__device__ __forceinline__ void sweep_int64(const Layout &a, int wave, int l, int b, int budget,
                                             int64_t tile_start) {
     const int64_t S = a.S;
     const int64_t *Uprev = reinterpret_cast<const int64_t *>(a.U[(l - 1) & 1]) +
@@ -492,7 +498,7 @@ __device__ __forceinline__ void sweep_int64(const Layout &a, int l, int b, int b
     const int r = a.r_idx ? a.r_idx[(int64_t)b * a.L + l] : 0;
     const int64_t *R = a.R + ((int64_t)b * a.nR + r) * S * S;
 
-    for (int64_t e = tile_start + threadIdx.x; e < tile_start + a.tile_e; e += blockDim.x) {
+    for (int64_t e = tile_start + wave * kWave + lane_id(); e < tile_start + a.tile_e; e += blockDim.x) {
         if (e > budget) continue;
         for (int64_t s0 = 0; s0 < S; s0 += CH) {
             int64_t best[CH];
@@ -604,7 +610,7 @@ __device__ __forceinline__ void sweep_fast_at(const Layout &a, int l, int b, int
                                               int64_t e_wave, int64_t s0) {
     using Cell = typename Store::Cell;
     constexpr int64_t kPerSlot = 8 / sizeof(Cell);     // cells per reserved 8-byte slot
-    const int lane = threadIdx.x & 63;
+    const int lane = lane_id();
     const int64_t e0 = e_wave + lane;
     if (s0 >= a.S) return;
     if (e_wave > budget) return;
@@ -716,9 +722,8 @@ __device__ __forceinline__ void sweep_fast_at(const Layout &a, int l, int b, int
 
 // Position of a wave in a workgroup of NG strategy groups x (waves / NG) budget sub-tiles.
 template <int TS, int TE, int NG, class Store, class BP>
-__device__ __forceinline__ void sweep_fast(const Layout &a, int l, int b, int budget,
+__device__ __forceinline__ void sweep_fast(const Layout &a, int wave, int l, int b, int budget,
                                            int64_t tile_start) {
-    const int wave = uniform(threadIdx.x >> 6);
     const int g = wave % NG;                       // strategy group of this wave
     const int esub = wave / NG;                    // budget sub-tile of this wave
     sweep_fast_at<TS, TE, Store, BP>(a, l, b, budget, tile_start + (int64_t)esub * (kWave * TE),
@@ -834,11 +839,10 @@ extern __shared__ uint32_t lds_cells[];
 // beyond what one workgroup of the row-sharing body covers (several strategy-group blocks along
 // grid.y).
 template <int TS, int TE, int NG, class BP>
-__device__ __forceinline__ void sweep_u32(const Layout &a, int l, int b, int budget,
+__device__ __forceinline__ void sweep_u32(const Layout &a, int wave, int l, int b, int budget,
                                           int64_t tile_start) {
     static_assert(TS <= 16, "one scalar load fetches the R keys of a row");
-    const int wave = uniform(threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
+    const int lane = lane_id();
     const int g = wave % NG;
     const int esub = wave / NG;
     const int64_t e0 = tile_start + (int64_t)esub * (kWave * TE) + lane;
@@ -1010,7 +1014,7 @@ constexpr int keep_rows(int cap) { return cap <= 64 ? 16 : 32; }
 // Only the survivors' keys live in LDS (keep_rows rows instead of S), which is what lets four
 // 8-wave workgroups share a CU at S = 128.
 template <int TS, int TE, int NG, class BP, class Cell>
-__device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, int budget,
+__device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, int b, int budget,
                                                  int64_t tile_start, bool add_stats) {
     // Cell: uint32_t (costs below 2^31, infinity = 2^31) or uint64_t (any cost up to the 2^62
     // precondition, infinity = 2^62).  Only RELATIVE costs enter the 32-bit keys, so the wide form
@@ -1022,8 +1026,7 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
     constexpr int kCols = kWave * TE;
     constexpr int kKeep = keep_rows(TS * NG);
     (void)budget;
-    const int g = uniform(threadIdx.x >> 6);       // wave = owner of rows g + NG * r = strategy group
-    const int lane = threadIdx.x & 63;
+    const int lane = lane_id();                    // (g: the wave = owner of rows g + NG * r = strategy group)
     const int64_t e0 = tile_start + lane;
     const int64_t s0 = (int64_t)g * TS;
 
@@ -1298,6 +1301,7 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int l, int b, 
 // the budget columns per lane; the 64-bit-key bodies then cover the same tile in UX steps.
 template <int TS, int TE, int NG, int WPE, class BP, int W, int UX, int SHARE>
 __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) {
+    const int wave = uniform(threadIdx.x >> 6);    // the only use of the thread-index register (see lane_id)
     const int b = a.b_off + blockIdx.z * a.b_step;
     // (one value per workgroup; said so, so that nothing derived from them counts as divergent)
     const int st = uniform(a.status[b]);
@@ -1318,9 +1322,9 @@ __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) 
     if (tile_start > budget) return;
     if (st == GALV_INSTANCE_OK_FAST_U32) {
         if constexpr (SHARE)
-            sweep_u32_shared<TS, TE * UX, NG, BP, uint32_t>(a, l, b, budget, tile_start, false);
+            sweep_u32_shared<TS, TE * UX, NG, BP, uint32_t>(a, wave, l, b, budget, tile_start, false);
         else
-            sweep_u32<TS, TE * UX, NG, BP>(a, l, b, budget, tile_start);
+            sweep_u32<TS, TE * UX, NG, BP>(a, wave, l, b, budget, tile_start);
     } else if (st == GALV_INSTANCE_OK_U32_WIDE) {
         // 8-byte cells: 64 columns at a time keep the rows within the registers the narrow form uses
         // (the preparation kernel grants this path to row-sharing variants only)
@@ -1328,17 +1332,17 @@ __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) 
             for (int h = 0; h < TE * UX; ++h) {
                 if (tile_start + h * kWave > budget) break;          // workgroup-uniform
                 if (h) __syncthreads();                              // the LDS of the part before is free again
-                sweep_u32_shared<TS, 1, NG, BP, uint64_t>(a, l, b, budget, tile_start + h * kWave, h > 0);
+                sweep_u32_shared<TS, 1, NG, BP, uint64_t>(a, wave, l, b, budget, tile_start + h * kWave, h > 0);
             }
         }
     } else if (st == GALV_INSTANCE_OK_FAST) {
         for (int h = 0; h < UX; ++h)
-            sweep_fast<TS, TE, NG, Narrow, BP>(a, l, b, budget, tile_start + h * (a.tile_e / UX));
+            sweep_fast<TS, TE, NG, Narrow, BP>(a, wave, l, b, budget, tile_start + h * (a.tile_e / UX));
     } else if (st == GALV_INSTANCE_OK_FAST_WIDE) {
         for (int h = 0; h < UX; ++h)
-            sweep_fast<TS, TE, NG, Wide, BP>(a, l, b, budget, tile_start + h * (a.tile_e / UX));
+            sweep_fast<TS, TE, NG, Wide, BP>(a, wave, l, b, budget, tile_start + h * (a.tile_e / UX));
     } else {
-        if (blockIdx.y == 0) sweep_int64<8>(a, l, b, budget, tile_start);
+        if (blockIdx.y == 0) sweep_int64<8>(a, wave, l, b, budget, tile_start);
     }
 }
 
@@ -2014,15 +2018,17 @@ galv_status_t galv_dp_create(const galv_dp_desc_t *desc, void *workspace_dev,
     h->n_side = 0;
     int n = (int)((desc->flags & GALV_DP_STREAMS_MASK) >> GALV_DP_STREAMS_SHIFT);
     if (n == 0) {
-        // Automatic, from the estimated duration of one layer's sweep (shape at ~2e13
-        // lane-operations/s).  Measured on MI355X with 4 hardware queues: sweeps of a few
-        // hundred microseconds gain 25-35 % from 9-10 streams (5-7 are nearly as good;
-        // multiples of 4 gain little), sweeps of tens of microseconds gain ~10 % from 2 and
-        // lose with more (host launch rate), shorter ones lose with any, and sweeps of a
-        // millisecond or more run at the arithmetic limit anyway and gain 2-5 % from 2.
-        const double us = 2.0 * desc->n_instances * ((double)desc->max_budget + 1) *
-                          desc->n_strategies * desc->n_strategies / 2e13 * 1e6;
-        n = us < 20.0 ? 1 : (us < 150.0 ? 2 : (us < 1000.0 ? 9 : 2));
+        // Automatic, from the estimated duration of one layer's sweep when it streams its
+        // 12 bytes per state at ~5.5 TB/s (what the pruned 32-bit-key sweep reaches; the estimate
+        // is within 2x of the measured single-stream launches of 12, 33, 145 and 290 us on the
+        // four named shapes).  Measured on MI355X with 4 hardware queues: sweeps of 150-300 us
+        // gain 10-30 % from 9 streams (5-7 are nearly as good; multiples of 4 gain little),
+        // sweeps of tens of microseconds gain ~10 % from 2 and lose with more (host launch
+        // rate), shorter ones lose with any, and sweeps near a millisecond or longer gain
+        // ~5 % from 2 (or 5) and less from 9.
+        const double us = 12.0 * desc->n_instances * ((double)desc->max_budget + 1) *
+                          desc->n_strategies / 5.5e12 * 1e6;
+        n = us < 20.0 ? 1 : (us < 100.0 ? 2 : (us < 600.0 ? 9 : 2));
     }
     if (n > desc->n_instances) n = desc->n_instances;
     if (n > 1 && desc->n_layers > 1) {
