@@ -123,6 +123,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--force-int64", action="store_true", help="time the general integer kernels")
     ap.add_argument("--no-u32", action="store_true", help="keep 64-bit keys (GALV_DP_NO_U32)")
+    ap.add_argument("--no-pack", action="store_true",
+                    help="rolling cost rows and plain back-pointers instead of the single packed table (GALV_DP_NO_PACK)")
     ap.add_argument("--bp-u8", action="store_true",
                     help="store back-pointers in one byte (GALV_DP_BP_U8): 9 instead of 12 B per state")
     ap.add_argument("--streams", type=int, default=0,
@@ -258,6 +260,7 @@ def run_config(cfg, args, torch, binding, workloads):
         w.name += f" with c and R x {args.c_scale}"
     base_flags = ((binding.GALV_DP_FORCE_INT64 if args.force_int64 else 0) |
                   (binding.GALV_DP_NO_U32 if args.no_u32 else 0) |
+                  (binding.GALV_DP_NO_PACK if args.no_pack else 0) |
                   (binding.GALV_DP_BP_U8 if args.bp_u8 else 0))
     dev = binding.upload(w)
     torch.cuda.synchronize()
@@ -338,7 +341,11 @@ def run_config(cfg, args, torch, binding, workloads):
     evaluated = sum(f * (int(e) + 1) * w.S * w.S for e, f in zip(w.budget, share))     # per layer
     ops = OPS_PER_CANDIDATE.get(int(status[0]), 0.0)
     sweep_ms, achieved = alu(solve_ms)
-    per_state = [BYTES_PER_STATE.get(int(st), 0) - (3 if args.bp_u8 else 0) for st in status]
+    # single packed table (the library's default with int32 back-pointers and S <= 256): 32-bit-key instances
+    # read and write one 4-byte word per state, plus one former minimum per budget column
+    packed = not (args.bp_u8 or args.no_pack) and w.S <= 256
+    per_state = [(4 + 4 + 2 * (4 if int(st) == 3 else 8) / w.S) if packed and int(st) in (3, 4)
+                 else BYTES_PER_STATE.get(int(st), 0) - (3 if args.bp_u8 else 0) for st in status]
     hbm_bytes = sum(p * (int(e) + 1) * w.S for p, e in zip(per_state, w.budget))   # per layer
     hbm_gbs = hbm_bytes / (sweep_ms * 1e-3) / 1e9
     # The same kernel with every layer as ONE launch on one stream: the per-launch figure that
@@ -392,6 +399,7 @@ def run_config(cfg, args, torch, binding, workloads):
         "config": {"workload": f"config {cfg} '{w.name}': B={w.B} L={w.L} S={w.S} "
                                f"E_max={w.E_max} budgets {int(w.budget.min())}..{int(w.budget.max())}",
                    "back_pointer_bytes": 1 if args.bp_u8 else 4,
+                   "single_packed_table": bool(packed and any(int(st) in (3, 4) for st in status)),
                    "internal_streams": "auto" if args.streams == 0 else args.streams,
                    "hip_graph_replay": bool(args.graph),
                    "cell_updates_per_batch": nominal, "exact_candidates_per_batch": exact,

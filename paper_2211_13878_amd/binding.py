@@ -26,6 +26,7 @@ GALV_DP_BP_U8 = 2
 GALV_DP_NO_U32 = 4
 GALV_DP_NO_PEEK = 8
 GALV_DP_FORCE_PEEK = 16
+GALV_DP_NO_PACK = 32
 
 
 def GALV_DP_STREAMS(n: int) -> int:

@@ -124,6 +124,9 @@ struct Layout {
     void *bp;             // argmin, un-shifted  [B][L-1][S][e_pad] of int32, or of uint8 (0xFF = none)
     int32_t bp_u8;        // 1: one-byte back-pointers
     int32_t peek;         // 1: the row-sharing sweep looks at two cells of a row before it fetches the row
+    int32_t packed;       // 1: instances on the 32-bit-key paths keep ONE table: the back-pointer word holds the
+                          //    reduced key (relative cost << k | argmin, all ones = unreachable) and the cost
+                          //    rows are replaced by one former minimum per budget column (see is_packed)
     int32_t synth_l1;     // 1: the 32-bit-key sweep makes up layer 0's cells (a constant per strategy)
                           //    when it sweeps layer 1, so layer 0's row is never written nor read
     int32_t b_off, b_step; // a sweep launch covers instances b_off + z * b_step (dealt over streams)
@@ -131,6 +134,7 @@ struct Layout {
     uint64_t *ck;         // per-mode c(l,s)     [B][L][S_pad]
     uint64_t *vlist;      // usable strategies of each layer, ascending: shift << 32 | s'; the last one repeats
                           // up to the row's end  [B][L][S_pad]
+    uint64_t *vcost;      // c(l, s') of the listed strategies, in the list's order (padded the same way)  [B][L][S_pad]
     int32_t *nvalid;      // how many of them    [B][L]
     uint32_t *dclamp;     // 32-bit-key path: largest R + 1, the clamp of relative costs  [B]
     int32_t *status;      // per instance        [B]
@@ -182,8 +186,18 @@ __device__ __forceinline__ int lead_kind(int st) {
     return 0;
 }
 
+// Whether instance status st keeps the single packed table (a handle-wide choice of kernels, and
+// the instance must be on a 32-bit-key path; one layer has no table at all).
+__device__ __forceinline__ bool is_packed(const Layout &a, int st) {
+    return a.packed && a.L > 1 && (st == GALV_INSTANCE_OK_FAST_U32 || st == GALV_INSTANCE_OK_U32_WIDE);
+}
+
 // Back-pointer of un-shifted cell idx, whichever width the handle stores.
-__device__ __forceinline__ int32_t load_bp(const Layout &a, int64_t idx) {
+__device__ __forceinline__ int32_t load_bp(const Layout &a, int st, int64_t idx) {
+    if (is_packed(a, st)) {
+        const uint32_t w = static_cast<const uint32_t *>(a.bp)[idx];
+        return w == 0xffffffffu ? -1 : (int32_t)(w & ((1u << a.k_bits) - 1u));
+    }
     if (a.bp_u8) {
         const uint8_t v = static_cast<const uint8_t *>(a.bp)[idx];
         return v == 0xFF ? -1 : (int32_t)v;
@@ -412,16 +426,23 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
     // of all S columns (a column that never fits is infinity everywhere).
     for (int64_t l = tid; l < L; l += kThreads) {
         uint64_t *lst = a.vlist + ((int64_t)b * L + l) * a.S_pad;
+        uint64_t *lc = a.vcost + ((int64_t)b * L + l) * a.S_pad;
         int n = 0;
         for (int s = 0; s < (int)S; ++s) {
             const int sh = m[l * S + s];
-            if (sh <= budget) lst[n++] = ((uint64_t)(uint32_t)sh << 32) | (uint32_t)s;
+            if (sh <= budget) {
+                lc[n] = (uint64_t)c[l * S + s];
+                lst[n++] = ((uint64_t)(uint32_t)sh << 32) | (uint32_t)s;
+            }
         }
         a.nvalid[(int64_t)b * L + l] = n;
         // Past the list's end its last entry repeats (it changes no minimum: min(x, x) = x), so
         // a sweep that walks a fixed number of entries needs no bound check; an empty list is
         // never walked.
-        for (int i = n; i < a.S_pad && n > 0; ++i) lst[i] = lst[n - 1];
+        for (int i = n; i < a.S_pad && n > 0; ++i) {
+            lst[i] = lst[n - 1];
+            lc[i] = lc[n - 1];
+        }
     }
 }
 
@@ -444,6 +465,7 @@ __global__ __launch_bounds__(kThreads) void init_kernel(Layout a, int fresh) {
         for (int64_t x = a.lead + x0; x < a.row; x += step) reinterpret_cast<int64_t *>(a.U[0] + base)[x] = c0;
         return;
     }
+    if (is_packed(a, st)) return;                  // no cost rows: layer 0 is made up, the sweeps test the shift
     const bool leads = fresh || a.lead_mode[b] != lead_kind(st);
     const bool u32_keys = st == GALV_INSTANCE_OK_FAST_U32 || st == GALV_INSTANCE_OK_U32_WIDE;
     const bool row0 = !(u32_keys && a.synth_l1 && a.L > 1);
@@ -1013,9 +1035,18 @@ constexpr int keep_rows(int cap) { return cap <= 64 ? 16 : 32; }
 //      rows, read again through the caches and turned into keys on the fly.
 // Only the survivors' keys live in LDS (keep_rows rows instead of S), which is what lets four
 // 8-wave workgroups share a CU at S = 128.
-template <int TS, int TE, int NG, class BP, class Cell>
+//
+// PACK: the table of back-pointers is the ONLY table.  The reduced key of a state already holds
+// both results, (cost relative to the column's former minimum Cmin) << k | argmin, and
+//     U_l[e'][s] = Cmin_l[e'] + (key >> k) + c(l, s),
+// so the sweep stores the key where the back-pointer goes (all ones = unreachable), one Cmin
+// per budget column beside it (rolling, in the space of the cost rows, which it replaces), and
+// the next layer rebuilds the cells of the rows it fetches: 4 bytes written and at most 4 read
+// per state instead of 8 and 4.  The backtrack masks the index out of the word.
+template <int TS, int TE, int NG, class BP, class Cell, bool PACK>
 __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, int b, int budget,
                                                  int64_t tile_start, bool add_stats) {
+    static_assert(!PACK || sizeof(BP) == 4, "a key needs the whole 32-bit word");
     // Cell: uint32_t (costs below 2^31, infinity = 2^31) or uint64_t (any cost up to the 2^62
     // precondition, infinity = 2^62).  Only RELATIVE costs enter the 32-bit keys, so the wide form
     // runs the same arithmetic and the same pruning; it moves 8-byte cells.
@@ -1042,6 +1073,13 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
     const ConstPtr<uint32_t> Rk =
         as_const(reinterpret_cast<const uint32_t *>(a.Rk + ((int64_t)b * a.nR + r_sel) * S * a.S_pad) + s0);
     const ConstPtr<uint64_t> ck = as_const(a.ck + ((int64_t)b * a.L + l) * a.S_pad + s0);
+    // PACK: the former layer's words (rows of e_pad, no lead: a column below the shift is tested
+    // for instead) and column minima, and this layer's column minima
+    const uint32_t *Wp = static_cast<const uint32_t *>(a.bp) +
+                         ((int64_t)b * (a.L - 1) + (l >= 2 ? l - 2 : 0)) * S * a.e_pad;
+    const Cell *Mp = reinterpret_cast<const Cell *>(a.U[(l - 1) & 1] + (int64_t)b * a.S_pad * a.row * 8);
+    Cell *Mn = reinterpret_cast<Cell *>(a.U[l & 1] + (int64_t)b * a.S_pad * a.row * 8) + e0;
+    const ConstPtr<uint64_t> vc = as_const(a.vcost + ((int64_t)b * a.L + (l - 1)) * a.S_pad);
     // the list is padded with repeats of its last entry up to S_pad = TS * NG entries
     const ConstPtr<uint64_t> vl = as_const(a.vlist + ((int64_t)b * a.L + (l - 1)) * a.S_pad);
     const int n = as_const(a.nvalid)[(int64_t)b * a.L + (l - 1)];
@@ -1051,13 +1089,32 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
     // is a constant per strategy, U_0[e'][s'] = c(0, s'), so when layer 1 is swept its cells are
     // made up here (infinity below the shift) instead of being read.
     const bool first = l == 1;                     // uniform
-    const ConstPtr<uint64_t> ck0 = as_const(a.ck + (int64_t)b * a.L * a.S_pad);
-    auto load_row = [&](uint64_t ent, Cell (&out)[TE]) {
+    // (cp = c(l-1, s'): what a made-up or rebuilt cell adds; unused for stored cells)
+    auto load_row = [&](uint64_t ent, Cell cp, Cell (&out)[TE]) {
         const uint32_t sp = (uint32_t)ent, shift = (uint32_t)(ent >> 32);
         if (first) {
-            const Cell c0 = (Cell)ck0[sp];
 #pragma unroll
-            for (int j = 0; j < TE; ++j) out[j] = e0 + j * kWave >= (int64_t)shift ? c0 : kInfCell;
+            for (int j = 0; j < TE; ++j) out[j] = e0 + j * kWave >= (int64_t)shift ? cp : kInfCell;
+        } else if constexpr (PACK) {
+            const uint32_t *w = Wp + (int64_t)sp * a.e_pad;
+            uint32_t wv[TE];
+            Cell mv[TE];
+            bool ok[TE];
+#pragma unroll
+            for (int j = 0; j < TE; ++j) {
+                const int64_t idx = e0 + j * kWave - (int64_t)shift;
+                ok[j] = idx >= 0;
+                const uint32_t x = ok[j] ? (uint32_t)idx : 0u;       // idx < e_pad <= 2^31 + 1024
+                wv[j] = w[x];
+                mv[j] = Mp[x];
+            }
+#pragma unroll
+            for (int j = 0; j < TE; ++j) {
+                // (the sum first, then a select between two values: a load used in one arm only
+                // would be moved into that arm, behind the other load's round trip)
+                const Cell cell = mv[j] + (Cell)(wv[j] >> k) + cp;
+                out[j] = ok[j] && wv[j] != 0xffffffffu ? cell : kInfCell;
+            }
         } else {
             const Cell *p = Up + (int64_t)sp * pitch - (int64_t)shift;
 #pragma unroll
@@ -1082,6 +1139,17 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
 
     if (g == 0 && lane == 0) count[0] = 0;
 
+    // This wave's rows: lane r (and lane 32 + r) fetches the list entry of row g + NG * r and that
+    // strategy's c(l-1, s'), which made-up and rebuilt cells add.  One vector load each, whose
+    // addresses depend on nothing but the workgroup's position: fetched as scalars where they are
+    // used, one row at a time, they form a chain of dependent round trips (entry, then c, then the
+    // cells) that costs more than everything else a tile does.  Rows that turn out to be needed
+    // get their entry broadcast from its lane.
+    static_assert(TS <= 32, "one lane per row and boundary");
+    const int my_row = (lane & 31) < TS ? (lane & 31) : TS - 1;      // (idle lanes repeat the last row)
+    const uint64_t my_ent = (a.vlist + ((int64_t)b * a.L + (l - 1)) * a.S_pad)[g + NG * my_row];
+    const Cell my_c0 = (Cell)(a.vcost + ((int64_t)b * a.L + (l - 1)) * a.S_pad)[g + NG * my_row];
+
     // Peek.  Every stored row is non-increasing along the budget axis (more memory never costs
     // more), so a row's cells in this tile are at least its cell in the tile's last column, and
     // every column minimum of the tile is at most Cmin_before = the minimum over the rows' cells
@@ -1103,41 +1171,26 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
     }
     if (n > 0 && a.peek) {
         // One gather for the whole wave: lane r (r < TS) fetches row r's cell in the column before
-        // the tile (for the first tile that is the infinity lead), lane 32 + r its cell in the last column.  The rows' addresses are wave-uniform
-        // scalars; each lane picks its own with a chain of selects.
-        Cell last_c[TS];
+        // the tile (below the shift: infinity), lane 32 + r its cell in the tile's last column.
         Cell first_min = kAllOnes;
-        static_assert(TS <= 32, "one lane per row and boundary");
-        const int my_row = lane & 31;
         const bool my_last = lane >= 32;
-        const Cell *my_p = Up;                     // any valid address for the idle lanes
-        Cell my_c0 = 0;
-        bool my_below = false;                     // (first layer) this lane's column lies below the row's shift
-#pragma unroll
-        for (int r = 0; r < TS; ++r) {
-            const uint64_t ent = vl[g + NG * r];
-            const uint32_t sp = (uint32_t)ent, shift = (uint32_t)(ent >> 32);
-            if (first) {
-                const Cell c0 = (Cell)ck0[sp];
-                if (my_row == r) {
-                    my_c0 = c0;
-                    my_below = tile_start + (my_last ? kCols - 1 : -1) < (int64_t)shift;
-                }
-            } else {
-                const Cell *p = Up + (int64_t)sp * pitch - (int64_t)shift;
-                if (my_row == r) my_p = p;
-            }
-        }
+        const uint32_t my_sp = (uint32_t)my_ent, my_shift = (uint32_t)(my_ent >> 32);
         Cell mine;
-        if (first)
-            mine = my_below ? kInfCell : my_c0;
-        else
-            mine = my_p[my_last ? kCols - 1 : -1];
-#pragma unroll
-        for (int r = 0; r < TS; ++r) {
-            first_min = min(first_min, read_lane(mine, r));
-            last_c[r] = read_lane(mine, 32 + r);
+        const int64_t idx = tile_start + (my_last ? kCols - 1 : -1) - (int64_t)my_shift;
+        if (first) {
+            mine = idx < 0 ? kInfCell : my_c0;     // this lane's column lies below the row's shift
+        } else if constexpr (PACK) {
+            const bool ok = idx >= 0;
+            const uint32_t x = ok ? (uint32_t)idx : 0u;
+            const uint32_t wv = Wp[(int64_t)my_sp * a.e_pad + x];
+            const Cell mv = Mp[x];
+            const Cell cell = mv + (Cell)(wv >> k) + my_c0;
+            mine = ok && wv != 0xffffffffu ? cell : kInfCell;
+        } else {
+            mine = Up[(int64_t)my_sp * pitch + (idx - tile_start)];   // (the lead holds infinity below the shift)
         }
+#pragma unroll
+        for (int r = 0; r < TS; ++r) first_min = min(first_min, read_lane(mine, r));
         uint32_t *peek = count + 2;                // rows fetched by the workgroup
         if (lane == 0) wave_min[g] = first_min;
         if (g == 0 && lane == 0) peek[0] = 0;
@@ -1147,13 +1200,10 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
         for (int w = 0; w < NG; ++w) cmin_first = min(cmin_first, read_lane(wave_min[w], 0));
         // an unreachable column before the tile (Cmin_before = infinity) bounds nothing: read every row
         const Cell limit = cmin_first < kInfCell ? cmin_first + (Cell)dmax : kAllOnes;
-        int mine_read = 0;
-#pragma unroll
-        for (int r = 0; r < TS; ++r)
-            if (g + NG * r < n && last_c[r] < limit) {
-                keep |= 1u << r;
-                ++mine_read;
-            }
+        // lane 32 + r holds row r's last-column cell and votes for its row
+        const bool my_keep = my_last && lane - 32 < TS && g + NG * (lane - 32) < n && mine < limit;
+        keep = (uint32_t)(__builtin_amdgcn_ballot_w64(my_keep) >> 32);
+        const int mine_read = __builtin_popcount(keep);
         if (lane == 0 && mine_read) atomicAdd(&peek[0], (uint32_t)mine_read);
     }
 
@@ -1162,13 +1212,58 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
         Cell pm[TE];
 #pragma unroll
         for (int j = 0; j < TE; ++j) pm[j] = kAllOnes;
+        if (PACK && !first) {
+            // Rebuilt cells: the words and column minima of kChunk rows are requested before the
+            // first of them is used, so the rows' round trips overlap (a row that is not read
+            // counts as unreachable: it leaves every minimum alone).
+            constexpr int kChunk = 4;
 #pragma unroll
-        for (int r = 0; r < TS; ++r) {
-            if (keep >> r & 1) {
-                load_row(vl[g + NG * r], rowc[r]);
-            } else {
+            for (int r0 = 0; r0 < TS; r0 += kChunk) {
+                uint32_t wv[kChunk][TE];
+                Cell mv[kChunk][TE];
 #pragma unroll
-                for (int j = 0; j < TE; ++j) rowc[r][j] = kAllOnes;          // leaves every minimum alone
+                for (int q = 0; q < kChunk; ++q) {
+                    const int r = r0 + q;
+                    if (r >= TS) break;
+#pragma unroll
+                    for (int j = 0; j < TE; ++j) {
+                        wv[q][j] = 0xffffffffu;
+                        mv[q][j] = 0;
+                    }
+                    if (keep >> r & 1) {
+                        const uint64_t e_r = read_lane(my_ent, r);
+                        const uint32_t *w = Wp + (int64_t)(uint32_t)e_r * a.e_pad;
+#pragma unroll
+                        for (int j = 0; j < TE; ++j) {
+                            const int64_t idx = e0 + j * kWave - (int64_t)(uint32_t)(e_r >> 32);
+                            const uint32_t x = idx >= 0 ? (uint32_t)idx : 0u;
+                            const uint32_t v = w[x];
+                            wv[q][j] = idx >= 0 ? v : 0xffffffffu;
+                            mv[q][j] = Mp[x];
+                        }
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < kChunk; ++q) {
+                    const int r = r0 + q;
+                    if (r >= TS) break;
+                    const Cell cp = read_lane(my_c0, r);
+#pragma unroll
+                    for (int j = 0; j < TE; ++j) {
+                        const Cell cell = mv[q][j] + (Cell)(wv[q][j] >> k) + cp;
+                        rowc[r][j] = wv[q][j] != 0xffffffffu ? cell : kInfCell;
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < TS; ++r) {
+                if (keep >> r & 1) {
+                    load_row(read_lane(my_ent, r), read_lane(my_c0, r), rowc[r]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < TE; ++j) rowc[r][j] = kAllOnes;          // leaves every minimum alone
+                }
             }
         }
 #pragma unroll
@@ -1186,7 +1281,6 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
             for (int j = 0; j < TE; ++j) cmin[j] = min(cmin[j], part[w * kCols + j * kWave + lane]);
 #pragma unroll
         for (int r = 0; r < TS; ++r) {
-            const int i = g + NG * r;
             if (keep >> r & 1) {                   // listed (the padding repeats a listed row) and read
                 uint32_t d[TE];                    // relative cost, clamped: all that a key needs
                 bool live = false;
@@ -1204,7 +1298,7 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
 #pragma unroll
                         for (int j = 0; j < TE; ++j)
                             keys[slot * kCols + j * kWave + lane] = d[j] << k;
-                        if (lane == 0) meta[slot] = (uint32_t)vl[i];
+                        if (lane == 0) meta[slot] = (uint32_t)read_lane(my_ent, r);
                     }
                 }
             }
@@ -1244,8 +1338,8 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
                 const uint64_t ea = vl[ia], eb = vl[ib];
                 spa[q] = uniform((int)(uint32_t)ea);     // (scalars already; said so for the compiler, which
                 spb[q] = uniform((int)(uint32_t)eb);     // merges them with the other branch's values)
-                load_row(ea, va[q]);
-                load_row(eb, vb[q]);
+                load_row(ea, (Cell)vc[ia], va[q]);
+                load_row(eb, (Cell)vc[ib], vb[q]);
             }
         };
         auto reduce_pair = [&](int q) {
@@ -1289,18 +1383,35 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
             for (int j = 0; j < TE; ++j) {
                 const bool alive = cmin[j] < kInfCell;
                 const uint32_t key = acc[s][j];
-                Un[(int64_t)s * pitch + j * kWave] = alive ? cmin[j] + (Cell)(key >> k) + cs : kInfCell;
-                __builtin_nontemporal_store((BP)(alive ? (int32_t)(key & mask) : -1),
-                                            &bp[(int64_t)s * a.e_pad + j * kWave]);
+                if constexpr (PACK) {
+                    // (a winning key is never all ones: the winner's relative cost is not clamped)
+                    bp[(int64_t)s * a.e_pad + j * kWave] = (BP)(alive ? key : 0xffffffffu);
+                } else {
+                    Un[(int64_t)s * pitch + j * kWave] = alive ? cmin[j] + (Cell)(key >> k) + cs : kInfCell;
+                    __builtin_nontemporal_store((BP)(alive ? (int32_t)(key & mask) : -1),
+                                                &bp[(int64_t)s * a.e_pad + j * kWave]);
+                }
             }
+        }
+    }
+    if constexpr (PACK) {
+        (void)mask;
+        (void)Un;
+        if (g == 0) {
+            // (of an unreachable column every word is all ones and this value is never used)
+#pragma unroll
+            for (int j = 0; j < TE; ++j) Mn[j * kWave] = cmin[j];
         }
     }
 }
 
 // UX: the 32-bit-key body keeps half-size accumulators, so it may take UX (1 or 2) times
 // the budget columns per lane; the 64-bit-key bodies then cover the same tile in UX steps.
-template <int TS, int TE, int NG, int WPE, class BP, int W, int UX, int SHARE>
+// PACK (row-sharing variants with int32 back-pointers): the 32-bit-key instances keep the single
+// packed table; the handle says so in Layout::packed and launches this instantiation.
+template <int TS, int TE, int NG, int WPE, class BP, int W, int UX, int SHARE, int PACK>
 __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) {
+    static_assert(!PACK || (SHARE && sizeof(BP) == 4), "the packed table needs the row-sharing body and 32-bit words");
     const int wave = uniform(threadIdx.x >> 6);    // the only use of the thread-index register (see lane_id)
     const int b = a.b_off + blockIdx.z * a.b_step;
     // (one value per workgroup; said so, so that nothing derived from them counts as divergent)
@@ -1322,7 +1433,7 @@ __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) 
     if (tile_start > budget) return;
     if (st == GALV_INSTANCE_OK_FAST_U32) {
         if constexpr (SHARE)
-            sweep_u32_shared<TS, TE * UX, NG, BP, uint32_t>(a, wave, l, b, budget, tile_start, false);
+            sweep_u32_shared<TS, TE * UX, NG, BP, uint32_t, PACK != 0>(a, wave, l, b, budget, tile_start, false);
         else
             sweep_u32<TS, TE * UX, NG, BP>(a, wave, l, b, budget, tile_start);
     } else if (st == GALV_INSTANCE_OK_U32_WIDE) {
@@ -1332,7 +1443,7 @@ __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) 
             for (int h = 0; h < TE * UX; ++h) {
                 if (tile_start + h * kWave > budget) break;          // workgroup-uniform
                 if (h) __syncthreads();                              // the LDS of the part before is free again
-                sweep_u32_shared<TS, 1, NG, BP, uint64_t>(a, wave, l, b, budget, tile_start + h * kWave, h > 0);
+                sweep_u32_shared<TS, 1, NG, BP, uint64_t, PACK != 0>(a, wave, l, b, budget, tile_start + h * kWave, h > 0);
             }
         }
     } else if (st == GALV_INSTANCE_OK_FAST) {
@@ -1353,6 +1464,16 @@ __device__ __forceinline__ int64_t last_layer_cost(const Layout &a, int b, int s
                                                    int64_t s) {
     const int64_t shift = a.m[((int64_t)b * a.L + (a.L - 1)) * a.S + s];
     if (shift > e) return kInf;
+    if (is_packed(a, st)) {
+        // U_{L-1}[e'][s] = Cmin[e'] + (key >> k) + c(L-1, s) with e' = e - shift
+        const int64_t x = e - shift;
+        const uint32_t w = static_cast<const uint32_t *>(a.bp)[(((int64_t)b * (a.L - 1) + (a.L - 2)) * a.S + s) * a.e_pad + x];
+        if (w == 0xffffffffu) return kInf;
+        const char *M = a.U[(a.L - 1) & 1] + (int64_t)b * a.S_pad * a.row * 8;
+        const int64_t cmin = st == GALV_INSTANCE_OK_U32_WIDE ? (int64_t)reinterpret_cast<const uint64_t *>(M)[x]
+                                                             : (int64_t)reinterpret_cast<const uint32_t *>(M)[x];
+        return cmin + (int64_t)(w >> a.k_bits) + a.c[((int64_t)b * a.L + (a.L - 1)) * a.S + s];
+    }
     const char *U = a.U[(a.L - 1) & 1] + ((int64_t)b * a.S_pad + s) * a.row * 8;
     const int64_t x = a.lead + e - shift;
     if (narrow_cells(st))
@@ -1390,13 +1511,15 @@ __global__ __launch_bounds__(kThreads) void final_kernel(Layout a, int64_t *best
         best_last[b] = last;
         a.last[b] = last;
         // every block of init_kernel has long finished: safe to record what the leads hold
-        a.lead_mode[b] = st < 0 ? 0 : lead_kind(st);
+        // (a packed instance keeps its column minima where the first row's lead was)
+        a.lead_mode[b] = st < 0 || is_packed(a, st) ? 0 : lead_kind(st);
     }
 }
 
 // Walk the un-shifted argmin table of instance b from (L-1, e, s) down to layer 0:
 // L dependent loads.  Writes the plan, or all -1 when s < 0.
 __device__ __forceinline__ void walk_plan(const Layout &a, int b, int64_t e, int s, int32_t *out) {
+    const int st = a.status[b];
     if (s < 0) {
         for (int l = 0; l < a.L; ++l) out[l] = -1;
         return;
@@ -1410,7 +1533,7 @@ __device__ __forceinline__ void walk_plan(const Layout &a, int b, int64_t e, int
             for (int q = 0; q < a.L; ++q) out[q] = -1;
             return;
         }
-        s = load_bp(a, (((int64_t)b * (a.L - 1) + (l - 1)) * a.S + s) * a.e_pad + e);
+        s = load_bp(a, st, (((int64_t)b * (a.L - 1) + (l - 1)) * a.S + s) * a.e_pad + e);
         if (s < 0 || s >= a.S) {
             for (int q = 0; q < a.L; ++q) out[q] = -1;
             return;
@@ -1469,6 +1592,7 @@ __global__ __launch_bounds__(kWave) void backtrack_kernel(Layout a, int32_t *pla
         return;
     }
     int64_t e = a.budget[b];
+    const int st = a.status[b];
     for (int l = a.L - 1; l >= 1; --l) {
         out[l] = s;
         e -= m_lds[(int64_t)l * a.S + s];
@@ -1476,7 +1600,7 @@ __global__ __launch_bounds__(kWave) void backtrack_kernel(Layout a, int32_t *pla
             for (int q = 0; q < a.L; ++q) out[q] = -1;
             return;
         }
-        s = load_bp(a, (((int64_t)b * (a.L - 1) + (l - 1)) * a.S + s) * a.e_pad + e);
+        s = load_bp(a, st, (((int64_t)b * (a.L - 1) + (l - 1)) * a.S + s) * a.e_pad + e);
         if (s < 0 || s >= a.S) {
             for (int q = 0; q < a.L; ++q) out[q] = -1;
             return;
@@ -1553,7 +1677,7 @@ __global__ __launch_bounds__(kThreads) void export_kernel(Layout a, int b, int64
         if (live && l >= 1) {
             const int64_t shift = a.m[((int64_t)b * a.L + l) * a.S + s];
             if (shift <= e)
-                v = load_bp(a, (((int64_t)b * (a.L - 1) + (l - 1)) * a.S + s) * a.e_pad + (e - shift));
+                v = load_bp(a, st, (((int64_t)b * (a.L - 1) + (l - 1)) * a.S + s) * a.e_pad + (e - shift));
         }
         dst[s] = v;
     }
@@ -1718,6 +1842,7 @@ using SweepFn = void (*)(Layout, int);
 struct VariantEntry {
     Variant v;
     SweepFn fn, fn_u8;     // int32 and one-byte back-pointers
+    SweepFn fn_pack;       // int32, single packed table (row-sharing variants; else null)
 };
 template <int TS, int TE, int NG, int WPE, int W, int UX, int SHARE>
 VariantEntry variant_entry() {
@@ -1725,9 +1850,12 @@ VariantEntry variant_entry() {
                   "strategy groups must divide the workgroup's waves");
     static_assert(!SHARE || W == NG, "the row-sharing body has one budget tile per workgroup");
     static_assert((UX == 1 || UX == 2) && TE * UX <= 4, "budget columns per lane");
+    SweepFn pack = nullptr;
+    if constexpr (SHARE != 0) pack = sweep_kernel<TS, TE, NG, WPE, int32_t, W, UX, SHARE, 1>;
     return {{TS, TE, NG, W, UX, SHARE},
-            sweep_kernel<TS, TE, NG, WPE, int32_t, W, UX, SHARE>,
-            sweep_kernel<TS, TE, NG, WPE, uint8_t, W, UX, SHARE>};
+            sweep_kernel<TS, TE, NG, WPE, int32_t, W, UX, SHARE, 0>,
+            sweep_kernel<TS, TE, NG, WPE, uint8_t, W, UX, SHARE, 0>,
+            pack};
 }
 
 const VariantEntry &pick_variant(int S) {
@@ -1765,7 +1893,7 @@ struct Plan {
     Variant var;
     SweepFn sweep;
     Layout lay;
-    size_t off_U[2], off_bp, off_Rk, off_ck, off_vlist, off_nvalid, off_status, off_last, off_dclamp,
+    size_t off_U[2], off_bp, off_Rk, off_ck, off_vlist, off_vcost, off_nvalid, off_status, off_last, off_dclamp,
         off_lead_mode, off_stats, total;
     int groups_y;
     unsigned lds_bytes;
@@ -1783,7 +1911,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
         return fail(GALV_ERR_INVALID_ARG, "n_strategies %d exceeds the limit %d", d->n_strategies,
                     kMaxS);
     if (d->flags & ~(GALV_DP_FORCE_INT64 | GALV_DP_BP_U8 | GALV_DP_NO_U32 | GALV_DP_NO_PEEK | GALV_DP_FORCE_PEEK |
-                     GALV_DP_STREAMS_MASK))
+                     GALV_DP_NO_PACK | GALV_DP_STREAMS_MASK))
         return fail(GALV_ERR_INVALID_ARG, "unknown flag bits");
     if (((d->flags & GALV_DP_STREAMS_MASK) >> GALV_DP_STREAMS_SHIFT) > (uint32_t)kMaxSide)
         return fail(GALV_ERR_INVALID_ARG, "at most %d internal streams", kMaxSide);
@@ -1799,8 +1927,10 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     memset(p, 0, sizeof *p);
     const VariantEntry &ve = pick_variant(d->n_strategies);
     const Variant v = ve.v;
-    p->sweep = u8 ? ve.fn_u8 : ve.fn;
+    const bool packed = v.share && !u8 && !(d->flags & GALV_DP_NO_PACK);
+    p->sweep = packed ? ve.fn_pack : (u8 ? ve.fn_u8 : ve.fn);
     Layout &a = p->lay;
+    a.packed = packed ? 1 : 0;
     a.B = d->n_instances;
     a.L = d->n_layers;
     a.S = d->n_strategies;
@@ -1856,6 +1986,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     p->off_Rk = take((size_t)a.B * a.nR * a.S * a.S_pad * sizeof(double) + 1024);
     p->off_ck = take((size_t)a.B * a.L * a.S_pad * sizeof(uint64_t));
     p->off_vlist = take((size_t)a.B * a.L * a.S_pad * sizeof(uint64_t) + 64);   // + slack: entries are fetched eight at a time
+    p->off_vcost = take((size_t)a.B * a.L * a.S_pad * sizeof(uint64_t) + 64);
     p->off_nvalid = take((size_t)a.B * a.L * sizeof(int32_t));
     p->off_status = take((size_t)a.B * sizeof(int32_t));
     p->off_last = take((size_t)a.B * sizeof(int32_t));
@@ -1877,6 +2008,7 @@ void bind_workspace(Layout &a, const Plan &p, char *ws) {
     a.Rk = reinterpret_cast<double *>(ws + p.off_Rk);
     a.ck = reinterpret_cast<uint64_t *>(ws + p.off_ck);
     a.vlist = reinterpret_cast<uint64_t *>(ws + p.off_vlist);
+    a.vcost = reinterpret_cast<uint64_t *>(ws + p.off_vcost);
     a.nvalid = reinterpret_cast<int32_t *>(ws + p.off_nvalid);
     a.status = reinterpret_cast<int32_t *>(ws + p.off_status);
     a.last = reinterpret_cast<int32_t *>(ws + p.off_last);

@@ -16,7 +16,7 @@ INF = binding.GALV_INF
 assert INF == oracle.INF
 # the three arithmetic paths a small-valued instance can be sent down: 32-bit integer keys
 # (default), 64-bit keys in 32-bit cells, general 64-bit integers
-ALL_PATHS = (0, binding.GALV_DP_NO_U32, binding.GALV_DP_FORCE_INT64)
+ALL_PATHS = (0, binding.GALV_DP_NO_PACK, binding.GALV_DP_NO_U32, binding.GALV_DP_FORCE_INT64)
 THREADS = max(1, min(16, os.cpu_count() or 1))      # oracle instances solved side by side
 
 
@@ -439,6 +439,43 @@ def test_call_order_and_reuse():
         assert torch.equal(x, y)
     with pytest.raises(binding.GalvError):
         sol.export_tables(5)
+
+
+def test_one_handle_through_every_storage_form():
+    """The same handle solves, in turn, problems that land on different arithmetic paths and
+    table forms (single packed table, narrow and wide cost rows with their infinity leads,
+    64-bit integers): whatever one solve leaves in the workspace must not leak into the next."""
+    shape = dict(B=3, L=6, S=23, E_max=900, nR=2)
+    kinds = {
+        "packed": dict(c_range=(0, 5000), r_range=(0, 300)),
+        "narrow rows": dict(c_range=(0, 5000), r_range=(0, 1 << 28)),
+        "packed, 64-bit minima": dict(c_range=(0, 1 << 40), r_range=(0, 300)),
+        "wide rows": dict(c_range=(0, 1 << 36), r_range=(0, 1 << 34)),
+        "int64": dict(c_range=(0, 1 << 58), r_range=(0, 1 << 57)),
+    }
+    expect = {"packed": binding.GALV_INSTANCE_OK_FAST_U32, "narrow rows": binding.GALV_INSTANCE_OK_FAST,
+              "packed, 64-bit minima": binding.GALV_INSTANCE_OK_U32_WIDE, "wide rows": binding.GALV_INSTANCE_OK_FAST_WIDE,
+              "int64": binding.GALV_INSTANCE_OK_INT64}
+    order = ["packed", "narrow rows", "packed", "packed, 64-bit minima", "wide rows", "packed, 64-bit minima",
+             "narrow rows", "int64", "packed", "wide rows", "packed"]
+    for flags in (binding.GALV_DP_FORCE_PEEK, binding.GALV_DP_NO_PACK):
+        sol = binding.Solver(shape["B"], shape["L"], shape["S"], shape["E_max"], shape["nR"], flags)
+        for step, kind in enumerate(order):
+            w = workloads.random_workload(7000 + step, shape["B"], shape["L"], shape["S"], shape["E_max"], nR=2,
+                                          m_range=(0, 200), infeasible=0.08, zero_diagonal=False, **kinds[kind])
+            w.budget[0] = shape["E_max"]
+            cost, last = sol.solve(*binding.upload(w))
+            plan = sol.backtrack()
+            assert (sol.status().cpu().numpy() == expect[kind]).all(), (step, kind)
+            for b in range(w.B):
+                ref = oracle.solve(*w.instance(b), want_C_last=True, want_bp=True)
+                assert int(cost[b]) == ref.best_cost and int(last[b]) == ref.best_last, (step, kind, b)
+                assert (plan[b].cpu().numpy() == ref.plan).all(), (step, kind, b)
+                C, bp = sol.export_tables(b)
+                Eb = int(w.budget[b])
+                assert (C.cpu().numpy()[:Eb + 1] == ref.C_last).all(), (step, kind, b)
+                assert (bp.cpu().numpy()[:, :Eb + 1] == ref.bp).all(), (step, kind, b)
+        sol.close()
 
 
 def test_runs_on_a_side_stream():

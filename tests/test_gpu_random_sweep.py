@@ -14,7 +14,8 @@ pytestmark = pytest.mark.gpu
 FLAGS = [0, binding.GALV_DP_NO_U32, binding.GALV_DP_FORCE_INT64, binding.GALV_DP_BP_U8,
          binding.GALV_DP_BP_U8 | binding.GALV_DP_NO_U32, binding.GALV_DP_STREAMS(3),
          binding.GALV_DP_STREAMS(3) | binding.GALV_DP_BP_U8,
-         binding.GALV_DP_FORCE_PEEK, binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_BP_U8 | binding.GALV_DP_STREAMS(2)]
+         binding.GALV_DP_FORCE_PEEK, binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_BP_U8 | binding.GALV_DP_STREAMS(2),
+         binding.GALV_DP_NO_PACK, binding.GALV_DP_NO_PACK | binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_STREAMS(2)]
 
 
 @pytest.mark.parametrize("seed", [11, 12, 13])
@@ -56,4 +57,4 @@ def test_random_sweep(seed):
                     assert (C.cpu().numpy()[:Eb + 1] == full[b].C_last).all(), (it, S, L, E, fl, b)
                     assert (bp.cpu().numpy()[:, :Eb + 1] == full[b].bp).all(), (it, S, L, E, fl, b)
             sol.close()
-    assert paths >= {0, 1, 2, 3}          # every arithmetic path was taken somewhere in the sweep
+    assert paths >= {0, 1, 2, 3, 4}          # every arithmetic path was taken somewhere in the sweep
