@@ -91,11 +91,15 @@ typedef struct {
                                   sweep is then bound by bytes; below that it is bound by latency
                                   and the extra dependent step costs more than it saves).  Results
                                   are identical either way.                                          */
-#define GALV_DP_NO_PACK 32u    /* 32-bit-key instances: keep the rolling cost rows and plain back-pointers
-                                  instead of the single packed table (by default, with int32
-                                  back-pointers and at most 256 strategies, the back-pointer word of
-                                  a state also carries its cost relative to the column's former
-                                  minimum, and no other table is written).  Results are identical.  */
+#define GALV_DP_NO_PACK 32u    /* 32-bit-key instances: always keep the rolling cost rows and plain
+                                  back-pointers (see GALV_DP_FORCE_PACK)                            */
+#define GALV_DP_FORCE_PACK 64u /* 32-bit-key instances, int32 back-pointers, at most 256 strategies:
+                                  keep a SINGLE table, in which the back-pointer word of a state also
+                                  carries its cost relative to the smallest former cost of its budget
+                                  column, plus one such minimum per column; no cost rows are written.
+                                  Half the bytes per state.  By default this is done when a layer has
+                                  enough workgroups to fill the chip (as for GALV_DP_FORCE_PEEK).
+                                  Results, exported tables included, are identical either way.       */
 #define GALV_DP_STREAMS_SHIFT 8 /* bits 8..12: how many internal streams the layer sweeps are   */
 #define GALV_DP_STREAMS_MASK 0x1f00u /* spread over; 0 = chosen from the shape, 1 = none, at most 16 */
 #define GALV_DP_STREAMS(n) ((uint32_t)(n) << GALV_DP_STREAMS_SHIFT)

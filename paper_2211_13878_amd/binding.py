@@ -27,6 +27,7 @@ GALV_DP_NO_U32 = 4
 GALV_DP_NO_PEEK = 8
 GALV_DP_FORCE_PEEK = 16
 GALV_DP_NO_PACK = 32
+GALV_DP_FORCE_PACK = 64
 
 
 def GALV_DP_STREAMS(n: int) -> int:

@@ -137,6 +137,8 @@ struct Layout {
     uint64_t *vcost;      // c(l, s') of the listed strategies, in the list's order (padded the same way)  [B][L][S_pad]
     int32_t *nvalid;      // how many of them    [B][L]
     uint32_t *dclamp;     // 32-bit-key path: largest R + 1, the clamp of relative costs  [B]
+    int32_t *hdr;         // what a sweep workgroup needs first, in one place: status, budget, usable strategies of
+                          // the former layer, clamp, transition matrix of the layer; 3 unused  [B][L][8]
     int32_t *status;      // per instance        [B]
     int32_t *last;        // best last strategy  [B]
     int32_t *lead_mode;   // whose infinity leads the rows hold (lead_kind), 0 none  [B]
@@ -386,6 +388,18 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
     }
     __syncthreads();
     const int st = status_s;
+    // One record per layer with what a sweep workgroup needs before anything else, so that it
+    // takes one load instead of a chain of them.  (The count of the former layer's usable
+    // strategies is filled in below, by the thread that builds that layer's list.)
+    for (int64_t l = tid; l < L; l += kThreads) {
+        int32_t *h = a.hdr + ((int64_t)b * L + l) * 8;
+        h[0] = st;
+        h[1] = budget;
+        h[2] = 0;
+        h[3] = (int32_t)a.dclamp[b];
+        h[4] = (ridx && l >= 1 && st >= 0) ? ridx[l] : 0;
+    }
+    __syncthreads();
     if (!narrow_cells(st) && st != GALV_INSTANCE_OK_FAST_WIDE && st != GALV_INSTANCE_OK_U32_WIDE) return;
 
     // R key = R * 2^k + s' (s' = row = former strategy); padded columns are +inf so
@@ -436,6 +450,7 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
             }
         }
         a.nvalid[(int64_t)b * L + l] = n;
+        if (l + 1 < L) a.hdr[((int64_t)b * L + l + 1) * 8 + 2] = n;
         // Past the list's end its last entry repeats (it changes no minimum: min(x, x) = x), so
         // a sweep that walks a fixed number of entries needs no bound check; an empty list is
         // never walked.
@@ -568,9 +583,9 @@ typedef double double8 __attribute__((ext_vector_type(8)));
 // `keep0`, `keep1` are the registers of the R group that is still being loaded while this
 // statement runs: naming them as (unused) inputs keeps their next use close, so the
 // register allocator has no reason to spill or move them while the load is in flight.
-template <int TE>
+template <int TE, class K0, class K1>
 __device__ __forceinline__ void minplus(double (&acc)[TE], const double (&v)[TE], double rk,
-                                        const double8 &keep0, const double8 &keep1) {
+                                        const K0 &keep0, const K1 &keep1) {
     static_assert(TE == 1 || TE == 2 || TE == 4, "budget columns per lane");
     if constexpr (TE == 1) {
         double t0;
@@ -619,6 +634,31 @@ __device__ __forceinline__ void rgroup_request(RGroup<2> &g, ConstPtr<double> p)
 __device__ __forceinline__ void rgroup_await(RGroup<1> &g) {
     asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(g.c[0]));
 }
+__device__ __forceinline__ double rgroup_key(const RGroup<1> &g, int x) { return g.c[0][x]; }
+__device__ __forceinline__ double rgroup_key(const RGroup<2> &g, int x) { return g.c[x / 8][x % 8]; }
+__device__ __forceinline__ const double8 &rgroup_keep0(const RGroup<1> &g) { return g.c[0]; }
+__device__ __forceinline__ const double8 &rgroup_keep1(const RGroup<1> &g) { return g.c[0]; }
+__device__ __forceinline__ const double8 &rgroup_keep0(const RGroup<2> &g) { return g.c[0]; }
+__device__ __forceinline__ const double8 &rgroup_keep1(const RGroup<2> &g) { return g.c[1]; }
+// 9 to 12 keys: 8 + 4 doubles.  (Two buffers of 16 would take 64 of the ~100 scalar registers;
+// the compiler then moves or spills registers that a load in flight still targets, which the
+// build refuses.)
+typedef double double4 __attribute__((ext_vector_type(4)));
+struct RGroupMid {
+    double8 lo;
+    double4 hi;
+};
+__device__ __forceinline__ void rgroup_request(RGroupMid &g, ConstPtr<double> p) {
+    asm volatile("s_load_dwordx16 %0, %2, 0x0\n\ts_load_dwordx8 %1, %2, 0x40"
+                 : "=&s"(g.lo), "=&s"(g.hi)
+                 : "s"(p));
+}
+__device__ __forceinline__ void rgroup_await(RGroupMid &g) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(g.lo), "+s"(g.hi));
+}
+__device__ __forceinline__ double rgroup_key(const RGroupMid &g, int x) { return x < 8 ? g.lo[x] : g.hi[x - 8]; }
+__device__ __forceinline__ const double8 &rgroup_keep0(const RGroupMid &g) { return g.lo; }
+__device__ __forceinline__ const double4 &rgroup_keep1(const RGroupMid &g) { return g.hi; }
 __device__ __forceinline__ void rgroup_await(RGroup<2> &g) {
     asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(g.c[0]), "+s"(g.c[1]));
 }
@@ -675,7 +715,8 @@ __device__ __forceinline__ void sweep_fast_at(const Layout &a, int l, int b, int
         static_assert((kDepth * kGroups) % 2 == 0, "buffer roles must repeat every loop trip");
         Cell v[kDepth][TE];
         int sps[kDepth];
-        RGroup<kChunks> buf[2];
+        using Group = std::conditional_t<(TS > 8 && TS <= 12), RGroupMid, RGroup<kChunks>>;
+        Group buf[2];
         // Requests are never conditional (past the end they repeat the last entry,
         // which is cached) so that no wait is needed where control flow joins.
         auto request = [&](int q, int i) {
@@ -700,8 +741,8 @@ __device__ __forceinline__ void sweep_fast_at(const Layout &a, int l, int b, int
 #pragma unroll
                 for (int x = 0; x < kGroup; ++x)
                     if (gr * kGroup + x < TS)
-                        minplus<TE>(acc[gr * kGroup + x], key, buf[t & 1].c[x / 8][x % 8],
-                                    buf[(t + 1) & 1].c[0], buf[(t + 1) & 1].c[kChunks - 1]);
+                        minplus<TE>(acc[gr * kGroup + x], key, rgroup_key(buf[t & 1], x),
+                                    rgroup_keep0(buf[(t + 1) & 1]), rgroup_keep1(buf[(t + 1) & 1]));
                 rgroup_await(buf[(t + 1) & 1]);
             }
         };
@@ -1045,7 +1086,16 @@ constexpr int keep_rows(int cap) { return cap <= 64 ? 16 : 32; }
 // per state instead of 8 and 4.  The backtrack masks the index out of the word.
 template <int TS, int TE, int NG, class BP, class Cell, bool PACK>
 __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, int b, int budget,
-                                                 int64_t tile_start, bool add_stats) {
+                                                 int64_t tile_start, bool add_stats, int n, uint32_t dmax,
+                                                 int r_sel, uint64_t my_ent, uint64_t my_c0_64) {
+    // n, dmax, r_sel: the former layer's usable strategies, the clamp and the layer's transition
+    // matrix, from the header record.  my_ent, my_c0_64: lane r (and lane 32 + r) holds the list
+    // entry of this wave's row g + NG * r and that strategy's c(l-1, s'), which made-up and
+    // rebuilt cells add; the kernel requests them before it knows anything else (their addresses
+    // depend on the workgroup's position only), so that they arrive together with the header.
+    // Fetched as scalars where they are used, one row at a time, they form a chain of dependent
+    // round trips (entry, then c, then the cells) that costs more than everything else a tile
+    // does.  Rows that turn out to be needed get their entry broadcast from its lane.
     static_assert(!PACK || sizeof(BP) == 4, "a key needs the whole 32-bit word");
     // Cell: uint32_t (costs below 2^31, infinity = 2^31) or uint64_t (any cost up to the 2^62
     // precondition, infinity = 2^62).  Only RELATIVE costs enter the 32-bit keys, so the wide form
@@ -1069,7 +1119,6 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
     Cell *Un = reinterpret_cast<Cell *>(a.U[l & 1]) + ((int64_t)b * a.S_pad + s0) * pitch +
                    a.lead + e0;
     BP *bp = static_cast<BP *>(a.bp) + (((int64_t)b * (a.L - 1) + (l - 1)) * S + s0) * a.e_pad + e0;
-    const int r_sel = a.r_idx ? a.r_idx[(int64_t)b * a.L + l] : 0;
     const ConstPtr<uint32_t> Rk =
         as_const(reinterpret_cast<const uint32_t *>(a.Rk + ((int64_t)b * a.nR + r_sel) * S * a.S_pad) + s0);
     const ConstPtr<uint64_t> ck = as_const(a.ck + ((int64_t)b * a.L + l) * a.S_pad + s0);
@@ -1082,8 +1131,7 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
     const ConstPtr<uint64_t> vc = as_const(a.vcost + ((int64_t)b * a.L + (l - 1)) * a.S_pad);
     // the list is padded with repeats of its last entry up to S_pad = TS * NG entries
     const ConstPtr<uint64_t> vl = as_const(a.vlist + ((int64_t)b * a.L + (l - 1)) * a.S_pad);
-    const int n = as_const(a.nvalid)[(int64_t)b * a.L + (l - 1)];
-    const uint32_t dmax = as_const(a.dclamp)[b];
+    const Cell my_c0 = (Cell)my_c0_64;
 
     // The shifted cells of one usable former strategy for this lane's columns.  Layer 0's table
     // is a constant per strategy, U_0[e'][s'] = c(0, s'), so when layer 1 is swept its cells are
@@ -1138,17 +1186,6 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
     for (int j = 0; j < TE; ++j) cmin[j] = kAllOnes;
 
     if (g == 0 && lane == 0) count[0] = 0;
-
-    // This wave's rows: lane r (and lane 32 + r) fetches the list entry of row g + NG * r and that
-    // strategy's c(l-1, s'), which made-up and rebuilt cells add.  One vector load each, whose
-    // addresses depend on nothing but the workgroup's position: fetched as scalars where they are
-    // used, one row at a time, they form a chain of dependent round trips (entry, then c, then the
-    // cells) that costs more than everything else a tile does.  Rows that turn out to be needed
-    // get their entry broadcast from its lane.
-    static_assert(TS <= 32, "one lane per row and boundary");
-    const int my_row = (lane & 31) < TS ? (lane & 31) : TS - 1;      // (idle lanes repeat the last row)
-    const uint64_t my_ent = (a.vlist + ((int64_t)b * a.L + (l - 1)) * a.S_pad)[g + NG * my_row];
-    const Cell my_c0 = (Cell)(a.vcost + ((int64_t)b * a.L + (l - 1)) * a.S_pad)[g + NG * my_row];
 
     // Peek.  Every stored row is non-increasing along the budget axis (more memory never costs
     // more), so a row's cells in this tile are at least its cell in the tile's last column, and
@@ -1298,7 +1335,10 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
 #pragma unroll
                         for (int j = 0; j < TE; ++j)
                             keys[slot * kCols + j * kWave + lane] = d[j] << k;
-                        if (lane == 0) meta[slot] = (uint32_t)read_lane(my_ent, r);
+                        // (broadcast with every lane active, not under the test for lane 0: a
+                        // register reloaded from a spill there holds lane 0's value only)
+                        const uint32_t sp_r = (uint32_t)read_lane(my_ent, r);
+                        if (lane == 0) meta[slot] = sp_r;
                     }
                 }
             }
@@ -1414,10 +1454,24 @@ __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) 
     static_assert(!PACK || (SHARE && sizeof(BP) == 4), "the packed table needs the row-sharing body and 32-bit words");
     const int wave = uniform(threadIdx.x >> 6);    // the only use of the thread-index register (see lane_id)
     const int b = a.b_off + blockIdx.z * a.b_step;
-    // (one value per workgroup; said so, so that nothing derived from them counts as divergent)
-    const int st = uniform(a.status[b]);
+    // The row-sharing body's list entries (see there): requested first, ahead of the header.
+    uint64_t my_ent = 0, my_c0 = 0;
+    if constexpr (SHARE != 0) {
+        const int lane = lane_id();
+        const int my_row = (lane & 31) < TS ? (lane & 31) : TS - 1;      // (idle lanes repeat the last row)
+        const int64_t at = ((int64_t)b * a.L + (l - 1)) * a.S_pad + wave + NG * my_row;
+        my_ent = a.vlist[at];
+        my_c0 = a.vcost[at];
+    }
+    // One record holds what the workgroup needs to begin with.
+    const ConstPtr<int32_t> hdr = as_const(a.hdr + ((int64_t)b * a.L + l) * 8);
+    const int st = hdr[0];
+    const int budget = hdr[1];
+    const int n_prev = hdr[2];
+    const uint32_t dmax = (uint32_t)hdr[3];
+    const int r_sel = hdr[4];
+    (void)n_prev, (void)dmax, (void)r_sel, (void)my_ent, (void)my_c0;
     if (st < 0) return;
-    const int budget = uniform(a.budget[b]);
 #if GALV_XCD_MAP
     // Workgroups go round-robin to the 8 XCDs in the order of their linear index, and grid.x is
     // a multiple of 8, so blockIdx.x & 7 names the XCD.  Each XCD takes a contiguous eighth of
@@ -1433,7 +1487,7 @@ __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) 
     if (tile_start > budget) return;
     if (st == GALV_INSTANCE_OK_FAST_U32) {
         if constexpr (SHARE)
-            sweep_u32_shared<TS, TE * UX, NG, BP, uint32_t, PACK != 0>(a, wave, l, b, budget, tile_start, false);
+            sweep_u32_shared<TS, TE * UX, NG, BP, uint32_t, PACK != 0>(a, wave, l, b, budget, tile_start, false, n_prev, dmax, r_sel, my_ent, my_c0);
         else
             sweep_u32<TS, TE * UX, NG, BP>(a, wave, l, b, budget, tile_start);
     } else if (st == GALV_INSTANCE_OK_U32_WIDE) {
@@ -1443,7 +1497,7 @@ __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) 
             for (int h = 0; h < TE * UX; ++h) {
                 if (tile_start + h * kWave > budget) break;          // workgroup-uniform
                 if (h) __syncthreads();                              // the LDS of the part before is free again
-                sweep_u32_shared<TS, 1, NG, BP, uint64_t, PACK != 0>(a, wave, l, b, budget, tile_start + h * kWave, h > 0);
+                sweep_u32_shared<TS, 1, NG, BP, uint64_t, PACK != 0>(a, wave, l, b, budget, tile_start + h * kWave, h > 0, n_prev, dmax, r_sel, my_ent, my_c0);
             }
         }
     } else if (st == GALV_INSTANCE_OK_FAST) {
@@ -1893,7 +1947,7 @@ struct Plan {
     Variant var;
     SweepFn sweep;
     Layout lay;
-    size_t off_U[2], off_bp, off_Rk, off_ck, off_vlist, off_vcost, off_nvalid, off_status, off_last, off_dclamp,
+    size_t off_U[2], off_bp, off_Rk, off_ck, off_vlist, off_vcost, off_nvalid, off_hdr, off_status, off_last, off_dclamp,
         off_lead_mode, off_stats, total;
     int groups_y;
     unsigned lds_bytes;
@@ -1911,7 +1965,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
         return fail(GALV_ERR_INVALID_ARG, "n_strategies %d exceeds the limit %d", d->n_strategies,
                     kMaxS);
     if (d->flags & ~(GALV_DP_FORCE_INT64 | GALV_DP_BP_U8 | GALV_DP_NO_U32 | GALV_DP_NO_PEEK | GALV_DP_FORCE_PEEK |
-                     GALV_DP_NO_PACK | GALV_DP_STREAMS_MASK))
+                     GALV_DP_NO_PACK | GALV_DP_FORCE_PACK | GALV_DP_STREAMS_MASK))
         return fail(GALV_ERR_INVALID_ARG, "unknown flag bits");
     if (((d->flags & GALV_DP_STREAMS_MASK) >> GALV_DP_STREAMS_SHIFT) > (uint32_t)kMaxSide)
         return fail(GALV_ERR_INVALID_ARG, "at most %d internal streams", kMaxSide);
@@ -1927,10 +1981,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     memset(p, 0, sizeof *p);
     const VariantEntry &ve = pick_variant(d->n_strategies);
     const Variant v = ve.v;
-    const bool packed = v.share && !u8 && !(d->flags & GALV_DP_NO_PACK);
-    p->sweep = packed ? ve.fn_pack : (u8 ? ve.fn_u8 : ve.fn);
     Layout &a = p->lay;
-    a.packed = packed ? 1 : 0;
     a.B = d->n_instances;
     a.L = d->n_layers;
     a.S = d->n_strategies;
@@ -1959,9 +2010,18 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     a.e_pad = (int64_t)round_up((size_t)a.E_max + 1, kEAlign);
     a.n_tiles = (int32_t)((a.E_max + a.tile_e) / a.tile_e);   // ceil((E_max+1)/tile_e)
     // measured: with ~1000 workgroups per layer (config 1) the peek costs 9 %, with ~6000 (config 2) it gains 14 %
-    a.peek = (int64_t)a.n_tiles * a.B >= 3072 ? 1 : 0;
+    const bool fills_chip = (int64_t)a.n_tiles * a.B >= 3072;
+    a.peek = fills_chip ? 1 : 0;
     if (d->flags & GALV_DP_NO_PEEK) a.peek = 0;
     if (d->flags & GALV_DP_FORCE_PEEK) a.peek = 1;
+    // The single packed table halves the bytes of a state but rebuilds every cell it reads from
+    // two loads: measured, it gains 15-25 % where the peek leaves few rows to read (configs 2-4)
+    // and loses 15 % where every row is read and latency binds (config 1): same switch as the peek.
+    bool packed = v.share && !u8 && fills_chip;
+    if (d->flags & GALV_DP_NO_PACK) packed = false;
+    if ((d->flags & GALV_DP_FORCE_PACK) && v.share && !u8) packed = true;
+    p->sweep = packed ? ve.fn_pack : (u8 ? ve.fn_u8 : ve.fn);
+    a.packed = packed ? 1 : 0;
     a.lead = (int64_t)round_up((size_t)a.E_max + 1, 64);
     a.row = a.lead + a.e_pad;
     p->var = v;
@@ -1991,6 +2051,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     p->off_status = take((size_t)a.B * sizeof(int32_t));
     p->off_last = take((size_t)a.B * sizeof(int32_t));
     p->off_dclamp = take((size_t)a.B * sizeof(uint32_t));
+    p->off_hdr = take((size_t)a.B * a.L * 8 * sizeof(int32_t));
     p->off_lead_mode = take((size_t)a.B * sizeof(int32_t));
     p->off_stats = take((size_t)a.B * (a.L > 1 ? a.L - 1 : 1) * a.n_tiles * 2 * sizeof(uint32_t));
     p->total = off;
@@ -2013,6 +2074,7 @@ void bind_workspace(Layout &a, const Plan &p, char *ws) {
     a.status = reinterpret_cast<int32_t *>(ws + p.off_status);
     a.last = reinterpret_cast<int32_t *>(ws + p.off_last);
     a.dclamp = reinterpret_cast<uint32_t *>(ws + p.off_dclamp);
+    a.hdr = reinterpret_cast<int32_t *>(ws + p.off_hdr);
     a.lead_mode = reinterpret_cast<int32_t *>(ws + p.off_lead_mode);
     a.stats = reinterpret_cast<uint32_t *>(ws + p.off_stats);
 }

@@ -18,7 +18,8 @@ def _solve(w, flags=0):
     return sol
 
 
-@pytest.mark.parametrize("S,flags", [(5, 0), (22, 0), (44, 0), (70, 0), (22, binding.GALV_DP_FORCE_INT64)])
+@pytest.mark.parametrize("S,flags", [(5, 0), (22, 0), (44, 0), (70, 0), (22, binding.GALV_DP_FORCE_INT64),
+                                     (22, binding.GALV_DP_FORCE_PACK), (130, binding.GALV_DP_FORCE_PACK | binding.GALV_DP_FORCE_PEEK)])
 def test_best_per_budget_matches_oracle_columns(S, flags):
     w = workloads.random_workload(300 + S, 3, 6, S, 900, nR=2, m_range=(0, 200), c_range=(0, 500),
                                   r_range=(0, 200), infeasible=0.1, zero_diagonal=False)
@@ -37,11 +38,12 @@ def test_best_per_budget_matches_oracle_columns(S, flags):
         assert (cost[b, 1:E_b + 1] <= cost[b, :E_b]).all()          # non-increasing in the budget
 
 
-def test_backtrack_queries_match_oracle_per_budget():
+@pytest.mark.parametrize("flags", [0, binding.GALV_DP_FORCE_PACK, binding.GALV_DP_FORCE_PACK | binding.GALV_DP_FORCE_PEEK])
+def test_backtrack_queries_match_oracle_per_budget(flags):
     w = workloads.random_workload(77, 4, 8, 22, 1500, nR=2, m_range=(0, 250), c_range=(0, 999),
                                   r_range=(0, 300), infeasible=0.1)
     w.budget[:] = [1500, 1200, 700, 1499]
-    sol = _solve(w)
+    sol = _solve(w, flags)
     rng = np.random.default_rng(5)
     inst, bud = [], []
     for b in range(w.B):

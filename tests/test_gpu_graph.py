@@ -11,13 +11,13 @@ from paper_2211_13878_amd import binding, workloads
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("n_streams", [1, 3])
-def test_capture_and_replay(n_streams):
+@pytest.mark.parametrize("n_streams,extra", [(1, 0), (3, 0), (2, binding.GALV_DP_FORCE_PACK | binding.GALV_DP_FORCE_PEEK)])
+def test_capture_and_replay(n_streams, extra):
     shapes = dict(B=6, L=10, S=40, E_max=1800)     # the variant that stages cells in LDS
     ws = [workloads.random_workload(800 + i, shapes["B"], shapes["L"], shapes["S"], shapes["E_max"], nR=2,
                                     m_range=(0, 250), c_range=(0, 5000), r_range=(0, 900), infeasible=0.06)
           for i in range(4)]
-    sol = binding.Solver(shapes["B"], shapes["L"], shapes["S"], shapes["E_max"], 2, binding.GALV_DP_STREAMS(n_streams))
+    sol = binding.Solver(shapes["B"], shapes["L"], shapes["S"], shapes["E_max"], 2, binding.GALV_DP_STREAMS(n_streams) | extra)
     dev = [t.clone() for t in binding.upload(ws[0])]
     # eager reference run (also warms up everything the capture must not do for the first time)
     sol.solve(*dev)

@@ -16,7 +16,8 @@ INF = binding.GALV_INF
 assert INF == oracle.INF
 # the three arithmetic paths a small-valued instance can be sent down: 32-bit integer keys
 # (default), 64-bit keys in 32-bit cells, general 64-bit integers
-ALL_PATHS = (0, binding.GALV_DP_NO_PACK, binding.GALV_DP_NO_U32, binding.GALV_DP_FORCE_INT64)
+# single packed table (forced: small shapes would not choose it), cost rows with 32-bit keys, 64-bit keys, int64
+ALL_PATHS = (binding.GALV_DP_FORCE_PACK, binding.GALV_DP_NO_PACK, binding.GALV_DP_NO_U32, binding.GALV_DP_FORCE_INT64)
 THREADS = max(1, min(16, os.cpu_count() or 1))      # oracle instances solved side by side
 
 
@@ -300,7 +301,7 @@ def test_random_shapes_ragged_tiles(S):
                                   c_range=(0, 50), r_range=(0, 20), infeasible=0.08,
                                   zero_diagonal=False)
     w.budget[0] = E_max
-    for flags in ALL_PATHS + (binding.GALV_DP_FORCE_PEEK,):
+    for flags in ALL_PATHS + (binding.GALV_DP_FORCE_PEEK, binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_FORCE_PACK):
         check_against_oracle(w, flags=flags, table_instances=[0, 1, 2])
 
 
@@ -309,7 +310,7 @@ def test_degenerate_sizes():
         w = workloads.random_workload(7, 4, L, S, E, m_range=(0, 3), c_range=(0, 5),
                                       r_range=(0, 5))
         w.budget[0] = E                     # at least one instance at the full width
-        for flags in ALL_PATHS + (binding.GALV_DP_FORCE_PEEK,):
+        for flags in ALL_PATHS + (binding.GALV_DP_FORCE_PEEK, binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_FORCE_PACK):
             check_against_oracle(w, flags=flags, table_instances=range(4))
 
 
@@ -372,7 +373,9 @@ def test_large_costs_with_small_transition_costs_keep_32bit_keys(S):
                                   r_range=(0, 3000), infeasible=0.08, zero_diagonal=False)
     w.c[3] = w.c[3] % 100000
     w.budget[:] = [700, 641, 577, 692]
-    for peek in (binding.GALV_DP_FORCE_PEEK, binding.GALV_DP_NO_PEEK):
+    PACK, ROWS = binding.GALV_DP_FORCE_PACK, binding.GALV_DP_NO_PACK
+    for peek in (binding.GALV_DP_FORCE_PEEK | PACK, binding.GALV_DP_NO_PEEK | PACK, binding.GALV_DP_FORCE_PEEK | ROWS,
+                 binding.GALV_DP_NO_PEEK | ROWS):
         cost, _, _, status = check_against_oracle(w, flags=peek, table_instances=[0, 1, 3])
         assert list(status) == [binding.GALV_INSTANCE_OK_U32_WIDE] * 3 + [binding.GALV_INSTANCE_OK_FAST_U32]
         assert (cost[cost < INF] > (1 << 33)).any()
@@ -387,12 +390,15 @@ def test_wide_integer_keys_when_nothing_can_be_pruned_and_at_the_cost_limit():
     w = workloads.random_workload(77, 3, 5, 44, 500, nR=2, m_range=(0, 120), c_range=(1 << 36, (1 << 36) + 9),
                                   r_range=(1000, 5000), infeasible=0.05, zero_diagonal=False)
     w.budget[0] = 500
-    _, _, _, status = check_against_oracle(w, flags=binding.GALV_DP_FORCE_PEEK, table_instances=[0, 1, 2])
-    assert (status == binding.GALV_INSTANCE_OK_U32_WIDE).all()
+    for flags in (binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_FORCE_PACK, binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_NO_PACK,
+                  binding.GALV_DP_FORCE_PACK):
+        _, _, _, status = check_against_oracle(w, flags=flags, table_instances=[0, 1, 2])
+        assert (status == binding.GALV_INSTANCE_OK_U32_WIDE).all()
     w = workloads.random_workload(78, 2, 4, 9, 300, m_range=(0, 90), c_range=(0, (1 << 59) - 1), r_range=(0, 99))
     w.budget[0] = 300
-    cost, _, _, status = check_against_oracle(w, table_instances=[0, 1])
-    assert (status == binding.GALV_INSTANCE_OK_U32_WIDE).all() and (cost[cost < INF] > (1 << 58)).any()
+    for flags in (binding.GALV_DP_FORCE_PACK, binding.GALV_DP_NO_PACK):
+        cost, _, _, status = check_against_oracle(w, flags=flags, table_instances=[0, 1])
+        assert (status == binding.GALV_INSTANCE_OK_U32_WIDE).all() and (cost[cost < INF] > (1 << 58)).any()
 
 
 def test_path_limits_by_transition_cost():
@@ -458,7 +464,8 @@ def test_one_handle_through_every_storage_form():
               "int64": binding.GALV_INSTANCE_OK_INT64}
     order = ["packed", "narrow rows", "packed", "packed, 64-bit minima", "wide rows", "packed, 64-bit minima",
              "narrow rows", "int64", "packed", "wide rows", "packed"]
-    for flags in (binding.GALV_DP_FORCE_PEEK, binding.GALV_DP_NO_PACK):
+    for flags in (binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_FORCE_PACK, binding.GALV_DP_FORCE_PACK,
+                  binding.GALV_DP_NO_PACK):
         sol = binding.Solver(shape["B"], shape["L"], shape["S"], shape["E_max"], shape["nR"], flags)
         for step, kind in enumerate(order):
             w = workloads.random_workload(7000 + step, shape["B"], shape["L"], shape["S"], shape["E_max"], nR=2,

@@ -15,7 +15,7 @@ FLAGS = [0, binding.GALV_DP_NO_U32, binding.GALV_DP_FORCE_INT64, binding.GALV_DP
          binding.GALV_DP_BP_U8 | binding.GALV_DP_NO_U32, binding.GALV_DP_STREAMS(3),
          binding.GALV_DP_STREAMS(3) | binding.GALV_DP_BP_U8,
          binding.GALV_DP_FORCE_PEEK, binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_BP_U8 | binding.GALV_DP_STREAMS(2),
-         binding.GALV_DP_NO_PACK, binding.GALV_DP_NO_PACK | binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_STREAMS(2)]
+         binding.GALV_DP_FORCE_PACK, binding.GALV_DP_FORCE_PACK | binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_STREAMS(2)]
 
 
 @pytest.mark.parametrize("seed", [11, 12, 13])
@@ -31,7 +31,7 @@ def test_random_sweep(seed):
         if S > 64:
             E = min(E, 600)
         mr = int(rng.choice([0, 1, 5, 50, 400]))
-        cr = int(rng.choice([0, 1, 9, 1000, 10**6, 10**8]))
+        cr = int(rng.choice([0, 1, 9, 1000, 10**6, 10**8, 10**11]))
         rr = int(rng.choice([0, 1, 9, 1000, 10**6, 2**27 - 1, 2**27, 2**29]))
         w = workloads.random_workload(int(rng.integers(1 << 30)), B, L, S, E, nR=int(rng.integers(1, 4)),
                                       m_range=(0, mr), c_range=(0, cr), r_range=(0, rr),

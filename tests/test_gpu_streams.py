@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 def test_parity_with_explicit_stream_counts(n_streams, B):
     w = workloads.random_workload(500 + B, B, 9, 23, 1500, nR=2, m_range=(0, 300), c_range=(0, 60),
                                   r_range=(0, 20), infeasible=0.08, zero_diagonal=False)
-    for extra in (0, binding.GALV_DP_FORCE_INT64, binding.GALV_DP_BP_U8):
+    for extra in (0, binding.GALV_DP_FORCE_PACK | binding.GALV_DP_FORCE_PEEK, binding.GALV_DP_FORCE_INT64, binding.GALV_DP_BP_U8):
         check_against_oracle(w, flags=binding.GALV_DP_STREAMS(n_streams) | extra,
                              table_instances=[0, B - 1])
 
@@ -25,7 +25,7 @@ def test_repeated_solves_and_caller_side_stream():
     solve must be ordered after the previous one's sweeps and before the reads that follow."""
     ws = [workloads.random_workload(600 + i, 6, 12, 22, 2000, m_range=(0, 250), c_range=(0, 1000),
                                     r_range=(0, 300), infeasible=0.05) for i in range(3)]
-    sol = binding.Solver(6, 12, 22, 2000, 1, binding.GALV_DP_STREAMS(3))
+    sol = binding.Solver(6, 12, 22, 2000, 1, binding.GALV_DP_STREAMS(3) | binding.GALV_DP_FORCE_PACK)
     side = torch.cuda.Stream()
     results = []
     devs = [binding.upload(w) for w in ws]

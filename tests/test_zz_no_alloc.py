@@ -51,7 +51,8 @@ def test_two_calls_in_a_row_second_smaller_then_a_wide_one():
         assert (ref[0] < binding.GALV_INF).any()
         assert same(via_static(w), ref), w.name
     # the other arithmetic paths and the one-byte back-pointers share the array too
-    for flags in (binding.GALV_DP_FORCE_INT64, binding.GALV_DP_NO_U32, binding.GALV_DP_BP_U8):
+    for flags in (binding.GALV_DP_FORCE_INT64, binding.GALV_DP_NO_U32, binding.GALV_DP_BP_U8,
+                  binding.GALV_DP_FORCE_PACK | binding.GALV_DP_FORCE_PEEK):
         assert same(via_static(big, flags), via_handle(big, flags))
     assert same(via_static(small), via_handle(small))
 
