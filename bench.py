@@ -19,9 +19,13 @@ searches/s and the exact candidate rate are reported beside it.
 `roofline` is for the layer-sweep kernel (the only kernel that matters: > 95 %
 of the time).  Two sides are computed per layer step, and the one that needs
 more time at its peak is the binding one (`roofline.bound`):
-  * HBM: 12 bytes per table state within the budgets (cost cell read, cost cell
-    written, int32 back-pointer written; 20 on the 64-bit-cell paths) against
-    8 TB/s;
+  * HBM: the table bytes of a state within the budgets, against 8 TB/s.  With the
+    single packed table (the library's choice when a layer fills the chip, as on
+    configurations 2-4) that is 8 bytes: one 32-bit word read and one written,
+    the word holding the back-pointer and the cost relative to its column's
+    former minimum, plus one minimum per budget column.  With rolling cost rows
+    (small shapes, --no-pack, one-byte back-pointers) it is 12: cost cell read,
+    cost cell written, int32 back-pointer written (20 with 64-bit cells);
   * ALU: the min-plus candidates the sweep evaluates (the library counts them:
     on the 32-bit-key path former strategies that cannot win any minimum of a
     tile are pruned; `candidates_evaluated_share`) times the lane-operations
@@ -34,8 +38,8 @@ solve, / (L-1).  With internal streams a layer is several overlapping launches,
 so that figure rests on event timing; `roofline.single_stream` is a second timed
 leg with one launch per layer, the kernel's own figure, which a kernel trace of
 `--streams 1` shows directly.
-`variant_bp_u8` is a third leg with one-byte back-pointers (same results, 9
-instead of 12 B/state).
+`variant_bp_u8` is a third leg with one-byte back-pointers (same results; rolling
+cost rows, 9 B/state: it saves workspace, not time, where the packed table applies).
 `cpu_baseline` times the serial CPU oracle (test infrastructure, never tuned) on a
 bounded sample of the same workload: one instance on one thread, and one instance
 per thread on the host cores this process may use.
@@ -67,7 +71,7 @@ BYTES_PER_STATE = {3: 4 + 4 + 4, 0: 4 + 4 + 4, 4: 8 + 8 + 4, 2: 8 + 8 + 4, 1: 8 
 # HBM bytes per sweep launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by the
 # same counter's reading for a 1 GiB copy: the `traffic_bytes_per_launch` line of
 # profiles/sweep_kernel_config<N>.md (tests/test_profiles.py keeps the two equal); None where not measured.
-MEASURED_TRAFFIC_BYTES = {3: 566244371, 4: 1260102263}
+MEASURED_TRAFFIC_BYTES = {3: 338545596, 4: 714232966}
 
 
 def cpu_baseline(w):
@@ -125,6 +129,7 @@ def main():
     ap.add_argument("--no-u32", action="store_true", help="keep 64-bit keys (GALV_DP_NO_U32)")
     ap.add_argument("--no-pack", action="store_true",
                     help="rolling cost rows and plain back-pointers instead of the single packed table (GALV_DP_NO_PACK)")
+    ap.add_argument("--force-pack", action="store_true", help="the single packed table whatever the shape (GALV_DP_FORCE_PACK)")
     ap.add_argument("--bp-u8", action="store_true",
                     help="store back-pointers in one byte (GALV_DP_BP_U8): 9 instead of 12 B per state")
     ap.add_argument("--streams", type=int, default=0,
@@ -261,6 +266,7 @@ def run_config(cfg, args, torch, binding, workloads):
     base_flags = ((binding.GALV_DP_FORCE_INT64 if args.force_int64 else 0) |
                   (binding.GALV_DP_NO_U32 if args.no_u32 else 0) |
                   (binding.GALV_DP_NO_PACK if args.no_pack else 0) |
+                  (binding.GALV_DP_FORCE_PACK if args.force_pack else 0) |
                   (binding.GALV_DP_BP_U8 if args.bp_u8 else 0))
     dev = binding.upload(w)
     torch.cuda.synchronize()
@@ -272,6 +278,8 @@ def run_config(cfg, args, torch, binding, workloads):
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    chosen = {}       # what the handle of the last timed leg chose (packed table, peek, streams)
 
     def timed(flags, steps, warmup):
         """K steps (solve + backtrack) on a fresh handle: wall ms per step, solve ms per step."""
@@ -309,6 +317,7 @@ def run_config(cfg, args, torch, binding, workloads):
         status = sol.status().cpu().numpy()
         stats = sol.stats().cpu().numpy()
         cost = sol.best_cost.cpu().numpy()
+        chosen.update(sol.config())
         sol.close()
         del sol
         torch.cuda.empty_cache()
@@ -328,6 +337,7 @@ def run_config(cfg, args, torch, binding, workloads):
 
     ms_per_step, solve_ms, status, cost, stats = timed(base_flags | binding.GALV_DP_STREAMS(args.streams),
                                                        args.steps, args.warmup)
+    main_leg = dict(chosen)
     # Share of the min-plus candidates the sweep evaluated: on the 32-bit-key path rows that cannot
     # win any minimum of a tile are left out (the library counts rows reduced / rows listed).
     share = [float(r) / float(n) if n > 0 else 1.0 for r, n, _ in stats]
@@ -343,7 +353,7 @@ def run_config(cfg, args, torch, binding, workloads):
     sweep_ms, achieved = alu(solve_ms)
     # single packed table (the library's default with int32 back-pointers and S <= 256): 32-bit-key instances
     # read and write one 4-byte word per state, plus one former minimum per budget column
-    packed = not (args.bp_u8 or args.no_pack) and w.S <= 256
+    packed = bool(main_leg["packed"])
     per_state = [(4 + 4 + 2 * (4 if int(st) == 3 else 8) / w.S) if packed and int(st) in (3, 4)
                  else BYTES_PER_STATE.get(int(st), 0) - (3 if args.bp_u8 else 0) for st in status]
     hbm_bytes = sum(p * (int(e) + 1) * w.S for p, e in zip(per_state, w.budget))   # per layer
@@ -372,7 +382,8 @@ def run_config(cfg, args, torch, binding, workloads):
     binding_obj = alu_obj if bound == "alu" else hbm_obj
     roofline = {"bound": bound, "kernel": "sweep_kernel", "achieved": binding_obj["achieved"],
                 "peak": binding_obj["peak"], "unit": binding_obj["unit"], "frac": binding_obj["frac"],
-                "traffic": None if (args.force_int64 or args.bp_u8) else MEASURED_TRAFFIC_BYTES.get(cfg),
+                "traffic": (MEASURED_TRAFFIC_BYTES.get(cfg) if base_flags == 0 and args.r_scale == 1 and args.c_scale == 1
+                            else None),
                 "launch_ms": sweep_ms,
                 "time_at_peak_us": {"alu": t_alu * 1e6, "hbm": t_hbm * 1e6},
                 "note": "per layer step of the whole batch, from events on the caller's stream around the "
@@ -400,7 +411,8 @@ def run_config(cfg, args, torch, binding, workloads):
                                f"E_max={w.E_max} budgets {int(w.budget.min())}..{int(w.budget.max())}",
                    "back_pointer_bytes": 1 if args.bp_u8 else 4,
                    "single_packed_table": bool(packed and any(int(st) in (3, 4) for st in status)),
-                   "internal_streams": "auto" if args.streams == 0 else args.streams,
+                   "internal_streams": main_leg["streams"],
+                   "peek_before_fetch": bool(main_leg["peek"]),
                    "hip_graph_replay": bool(args.graph),
                    "cell_updates_per_batch": nominal, "exact_candidates_per_batch": exact,
                    "table_states_per_batch": states},
@@ -418,7 +430,7 @@ def run_config(cfg, args, torch, binding, workloads):
         "roofline": roofline,
     }
     if not (args.bp_u8 or args.force_int64 or args.no_extra_legs) and w.S <= 255:
-        # storage variant, same results: one-byte back-pointers (9 instead of 12 B per state)
+        # storage variant, same results: one-byte back-pointers (rolling cost rows, 9 B per state)
         ms_u8, _, _, cost_u8, _ = timed(binding.GALV_DP_BP_U8 | binding.GALV_DP_STREAMS(args.streams),
                                      max(2, args.steps // 2), 1)
         assert (cost_u8 == cost).all()

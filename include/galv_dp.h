@@ -233,6 +233,16 @@ galv_status_t galv_dp_get_status(galv_dp_t *h, int32_t *status_dev, void *stream
 galv_status_t galv_dp_get_stats(galv_dp_t *h, int64_t *stats_dev, void *stream);
 
 /*
+ * What galv_dp_create chose for this handle from the shape and the flags (host call, no GPU work):
+ *   config [4] HOST int32  [0] 1 if 32-bit-key instances keep the single packed table (see
+ *                              GALV_DP_FORCE_PACK), [1] 1 if the sweep peeks before it fetches a
+ *                              row (GALV_DP_FORCE_PEEK), [2] internal streams, [3] budget columns
+ *                              per sweep workgroup.
+ * For benchmarks and tests that account for bytes moved; results never depend on any of it.
+ */
+galv_status_t galv_dp_get_config(const galv_dp_t *h, int32_t *config);
+
+/*
  * Outer loop of Algorithm 1 ("Optimization Workflow" of section 3.3) over a window of
  * candidate batch sizes, on the device, from stage optima that galv_dp_solve_batched wrote.
  * For batch size ib and pipeline degree P = pp_degree[ip] the time cost is the sum of its P

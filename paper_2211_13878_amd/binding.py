@@ -40,7 +40,7 @@ GALV_INSTANCE_BAD_VALUE = -1
 
 EXPORTS = ("galv_dp_workspace_bytes", "galv_dp_create", "galv_dp_solve_batched",
            "galv_dp_backtrack", "galv_dp_solve_static", "galv_dp_best_per_budget", "galv_dp_backtrack_queries",
-           "galv_dp_export_tables", "galv_dp_get_status", "galv_dp_get_stats", "galv_alg1_reduce",
+           "galv_dp_export_tables", "galv_dp_get_status", "galv_dp_get_stats", "galv_dp_get_config", "galv_alg1_reduce",
            "galv_dp_coarsen", "galv_dp_expand_plan",
            "galv_dp_destroy", "galv_dp_last_error", "galv_dp_build_stamp")
 
@@ -90,6 +90,7 @@ def load_library() -> ctypes.CDLL:
         lib.galv_dp_export_tables.argtypes = [vp, i32, vp, vp, vp]
         lib.galv_dp_get_status.argtypes = [vp, vp, vp]
         lib.galv_dp_get_stats.argtypes = [vp, vp, vp]
+        lib.galv_dp_get_config.argtypes = [vp, ctypes.POINTER(i32)]
         lib.galv_alg1_reduce.argtypes = [i32, i32, ctypes.POINTER(i32), vp, vp, i32, i32, vp, vp, vp]
         lib.galv_dp_coarsen.argtypes = [i32] * 6 + [vp] * 10
         lib.galv_dp_expand_plan.argtypes = [i32, i32, i32, vp, vp, vp]
@@ -198,6 +199,13 @@ def galv_dp_get_status(h, status, stream=None):
 
 def galv_dp_get_stats(h, stats, stream=None):
     _check(load_library().galv_dp_get_stats(h, _dev_ptr(stats, torch.int64), _stream_ptr(stream)))
+
+
+def galv_dp_get_config(h):
+    """(packed table, peek, internal streams, budget columns per workgroup) as the handle chose them."""
+    out = (ctypes.c_int32 * 4)()
+    _check(load_library().galv_dp_get_config(h, out))
+    return tuple(int(x) for x in out)
 
 
 # galv_alg1_state_t as six int32 words would misread the int64 fields; it is moved as raw bytes.
@@ -313,6 +321,10 @@ class Solver:
         st = torch.empty((self.B, 3), dtype=torch.int64, device=self.device)
         galv_dp_get_stats(self.handle, st, stream)
         return st
+
+    def config(self):
+        """dict: packed, peek, streams, tile_columns (see galv_dp_get_config)."""
+        return dict(zip(("packed", "peek", "streams", "tile_columns"), galv_dp_get_config(self.handle)))
 
     def close(self):
         if self.handle is not None:

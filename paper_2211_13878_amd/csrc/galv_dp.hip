@@ -1116,9 +1116,10 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
     const int64_t pitch = a.row * (8 / (int64_t)sizeof(Cell));   // cells between the rows of two strategies
     const Cell *Up = reinterpret_cast<const Cell *>(a.U[(l - 1) & 1]) +
                      (int64_t)b * a.S_pad * pitch + a.lead + tile_start;
-    Cell *Un = reinterpret_cast<Cell *>(a.U[l & 1]) + ((int64_t)b * a.S_pad + s0) * pitch +
-                   a.lead + e0;
-    BP *bp = static_cast<BP *>(a.bp) + (((int64_t)b * (a.L - 1) + (l - 1)) * S + s0) * a.e_pad + e0;
+    // (wave-uniform: the first column of the tile in this wave's first output row)
+    Cell *Un_tile = reinterpret_cast<Cell *>(a.U[l & 1]) + ((int64_t)b * a.S_pad + s0) * pitch +
+                    a.lead + tile_start;
+    BP *bp_tile = static_cast<BP *>(a.bp) + (((int64_t)b * (a.L - 1) + (l - 1)) * S + s0) * a.e_pad + tile_start;
     const ConstPtr<uint32_t> Rk =
         as_const(reinterpret_cast<const uint32_t *>(a.Rk + ((int64_t)b * a.nR + r_sel) * S * a.S_pad) + s0);
     const ConstPtr<uint64_t> ck = as_const(a.ck + ((int64_t)b * a.L + l) * a.S_pad + s0);
@@ -1127,7 +1128,7 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
     const uint32_t *Wp = static_cast<const uint32_t *>(a.bp) +
                          ((int64_t)b * (a.L - 1) + (l >= 2 ? l - 2 : 0)) * S * a.e_pad;
     const Cell *Mp = reinterpret_cast<const Cell *>(a.U[(l - 1) & 1] + (int64_t)b * a.S_pad * a.row * 8);
-    Cell *Mn = reinterpret_cast<Cell *>(a.U[l & 1] + (int64_t)b * a.S_pad * a.row * 8) + e0;
+    Cell *Mn_tile = reinterpret_cast<Cell *>(a.U[l & 1] + (int64_t)b * a.S_pad * a.row * 8) + tile_start;
     const ConstPtr<uint64_t> vc = as_const(a.vcost + ((int64_t)b * a.L + (l - 1)) * a.S_pad);
     // the list is padded with repeats of its last entry up to S_pad = TS * NG entries
     const ConstPtr<uint64_t> vl = as_const(a.vlist + ((int64_t)b * a.L + (l - 1)) * a.S_pad);
@@ -1262,11 +1263,6 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
                 for (int q = 0; q < kChunk; ++q) {
                     const int r = r0 + q;
                     if (r >= TS) break;
-#pragma unroll
-                    for (int j = 0; j < TE; ++j) {
-                        wv[q][j] = 0xffffffffu;
-                        mv[q][j] = 0;
-                    }
                     if (keep >> r & 1) {
                         const uint64_t e_r = read_lane(my_ent, r);
                         const uint32_t *w = Wp + (int64_t)(uint32_t)e_r * a.e_pad;
@@ -1284,11 +1280,16 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
                 for (int q = 0; q < kChunk; ++q) {
                     const int r = r0 + q;
                     if (r >= TS) break;
-                    const Cell cp = read_lane(my_c0, r);
+                    if (keep >> r & 1) {           // (wave-uniform: most rows are not read at all)
+                        const Cell cp = read_lane(my_c0, r);
 #pragma unroll
-                    for (int j = 0; j < TE; ++j) {
-                        const Cell cell = mv[q][j] + (Cell)(wv[q][j] >> k) + cp;
-                        rowc[r][j] = wv[q][j] != 0xffffffffu ? cell : kInfCell;
+                        for (int j = 0; j < TE; ++j) {
+                            const Cell cell = mv[q][j] + (Cell)(wv[q][j] >> k) + cp;
+                            rowc[r][j] = wv[q][j] != 0xffffffffu ? cell : kInfCell;
+                        }
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < TE; ++j) rowc[r][j] = kAllOnes;      // leaves every minimum alone
                     }
                 }
             }
@@ -1423,24 +1424,27 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
             for (int j = 0; j < TE; ++j) {
                 const bool alive = cmin[j] < kInfCell;
                 const uint32_t key = acc[s][j];
+                // (wave-uniform row address + the lane's offset: no per-store address arithmetic)
+                BP *bp_row = bp_tile + (int64_t)s * a.e_pad;
                 if constexpr (PACK) {
                     // (a winning key is never all ones: the winner's relative cost is not clamped)
-                    bp[(int64_t)s * a.e_pad + j * kWave] = (BP)(alive ? key : 0xffffffffu);
+                    bp_row[(uint32_t)lane + j * kWave] = (BP)(alive ? key : 0xffffffffu);
                 } else {
-                    Un[(int64_t)s * pitch + j * kWave] = alive ? cmin[j] + (Cell)(key >> k) + cs : kInfCell;
+                    Cell *un_row = Un_tile + (int64_t)s * pitch;
+                    un_row[(uint32_t)lane + j * kWave] = alive ? cmin[j] + (Cell)(key >> k) + cs : kInfCell;
                     __builtin_nontemporal_store((BP)(alive ? (int32_t)(key & mask) : -1),
-                                                &bp[(int64_t)s * a.e_pad + j * kWave]);
+                                                &bp_row[(uint32_t)lane + j * kWave]);
                 }
             }
         }
     }
     if constexpr (PACK) {
         (void)mask;
-        (void)Un;
+        (void)Un_tile;
         if (g == 0) {
             // (of an unreachable column every word is all ones and this value is never used)
 #pragma unroll
-            for (int j = 0; j < TE; ++j) Mn[j * kWave] = cmin[j];
+            for (int j = 0; j < TE; ++j) Mn_tile[(uint32_t)lane + j * kWave] = cmin[j];
         }
     }
 }
@@ -2375,6 +2379,16 @@ galv_status_t galv_dp_get_stats(galv_dp_t *h, int64_t *stats_dev, void *stream) 
     if (!h->solved) return fail(GALV_ERR_STATE, "statistics before a successful solve");
     stats_kernel<<<h->lay.B, kThreads, 0, static_cast<hipStream_t>(stream)>>>(h->lay, stats_dev);
     HIP_TRY(hipGetLastError());
+    return GALV_OK;
+}
+
+galv_status_t galv_dp_get_config(const galv_dp_t *h, int32_t *config) {
+    if (!h) return fail(GALV_ERR_INVALID_ARG, "handle is NULL");
+    if (!config) return fail(GALV_ERR_INVALID_ARG, "config is NULL");
+    config[0] = h->lay.packed;
+    config[1] = h->lay.peek && h->var.share ? 1 : 0;
+    config[2] = h->n_side > 1 ? h->n_side : 1;
+    config[3] = h->lay.tile_e;
     return GALV_OK;
 }
 
