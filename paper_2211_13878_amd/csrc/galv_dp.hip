@@ -1129,9 +1129,6 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
                          ((int64_t)b * (a.L - 1) + (l >= 2 ? l - 2 : 0)) * S * a.e_pad;
     const Cell *Mp = reinterpret_cast<const Cell *>(a.U[(l - 1) & 1] + (int64_t)b * a.S_pad * a.row * 8);
     Cell *Mn_tile = reinterpret_cast<Cell *>(a.U[l & 1] + (int64_t)b * a.S_pad * a.row * 8) + tile_start;
-    const ConstPtr<uint64_t> vc = as_const(a.vcost + ((int64_t)b * a.L + (l - 1)) * a.S_pad);
-    // the list is padded with repeats of its last entry up to S_pad = TS * NG entries
-    const ConstPtr<uint64_t> vl = as_const(a.vlist + ((int64_t)b * a.L + (l - 1)) * a.S_pad);
     const Cell my_c0 = (Cell)my_c0_64;
 
     // The shifted cells of one usable former strategy for this lane's columns.  Layer 0's table
@@ -1312,62 +1309,85 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
         for (int j = 0; j < TE; ++j) part[g * kCols + j * kWave + lane] = pm[j];
     }
     __syncthreads();
+    // With the column minimum known, a row's relative costs, clamped: all that its keys need.  A
+    // row that is clamped in every reachable column of the tile is dropped; the others go on the
+    // list (keys and strategy index), at the slot `counter` hands out.
+    auto append_row = [&](int r, const Cell (&cells)[TE], uint32_t *counter) {
+        uint32_t d[TE];
+        bool live = false;
+#pragma unroll
+        for (int j = 0; j < TE; ++j) {
+            const Cell rel = cells[j] - cmin[j];
+            d[j] = (uint32_t)min(rel, (Cell)dmax);
+            live |= rel < (Cell)dmax && cmin[j] < kInfCell;
+        }
+        if (__builtin_amdgcn_ballot_w64(live) != 0) {        // wave-uniform
+            uint32_t slot = 0;
+            if (lane == 0) slot = atomicAdd(counter, 1u);
+            slot = (uint32_t)uniform((int)slot);
+            if (slot < (uint32_t)kKeep) {
+#pragma unroll
+                for (int j = 0; j < TE; ++j) keys[slot * kCols + j * kWave + lane] = d[j] << k;
+                // (broadcast with every lane active, not under the test for lane 0: a register
+                // reloaded from a spill there holds lane 0's value only)
+                const uint32_t sp_r = (uint32_t)read_lane(my_ent, r);
+                if (lane == 0) meta[slot] = sp_r;
+            }
+        }
+    };
     if (n > 0) {
 #pragma unroll
         for (int w = 0; w < NG; ++w)
 #pragma unroll
             for (int j = 0; j < TE; ++j) cmin[j] = min(cmin[j], part[w * kCols + j * kWave + lane]);
 #pragma unroll
-        for (int r = 0; r < TS; ++r) {
-            if (keep >> r & 1) {                   // listed (the padding repeats a listed row) and read
-                uint32_t d[TE];                    // relative cost, clamped: all that a key needs
-                bool live = false;
-#pragma unroll
-                for (int j = 0; j < TE; ++j) {
-                    const Cell rel = rowc[r][j] - cmin[j];
-                    d[j] = (uint32_t)min(rel, (Cell)dmax);
-                    live |= rel < (Cell)dmax && cmin[j] < kInfCell;
-                }
-                if (__builtin_amdgcn_ballot_w64(live) != 0) {        // wave-uniform
-                    uint32_t slot = 0;
-                    if (lane == 0) slot = atomicAdd(&count[0], 1u);
-                    slot = (uint32_t)uniform((int)slot);
-                    if (slot < (uint32_t)kKeep) {
-#pragma unroll
-                        for (int j = 0; j < TE; ++j)
-                            keys[slot * kCols + j * kWave + lane] = d[j] << k;
-                        // (broadcast with every lane active, not under the test for lane 0: a
-                        // register reloaded from a spill there holds lane 0's value only)
-                        const uint32_t sp_r = (uint32_t)read_lane(my_ent, r);
-                        if (lane == 0) meta[slot] = sp_r;
-                    }
-                }
-            }
-        }
+        for (int r = 0; r < TS; ++r)
+            if (keep >> r & 1) append_row(r, rowc[r], count);   // listed (the padding repeats a listed row) and read
+        if (g == 0 && lane == 0) count[1] = 0;     // the counter of the pass after this one
     }
     __syncthreads();
-    if (s0 >= S) return;                           // an idle strategy group has done its share of the rows
 
-    const int nsurv = n > 0 ? uniform((int)count[0]) : 0;
-    if (g == 0 && lane == 0) {                     // statistics: how much the pruning removed
-        uint32_t *st = a.stats + 2 * (((int64_t)b * (a.L - 1) + (l - 1)) * a.n_tiles +
-                                      (uint32_t)tile_start / (uint32_t)a.tile_e);
-        const uint32_t rows = (uint32_t)(nsurv <= kKeep ? nsurv : n) << 16 | (uint32_t)n;
-        const uint32_t fetched = n > 0 ? count[2] : 0u;
-        st[0] = add_stats ? st[0] + rows : rows;   // (a tile swept in several parts adds them up)
-        st[1] = add_stats ? st[1] + fetched : fetched;
+    // The list holds the rows that matter, or it has overflowed (transition costs that dwarf the
+    // spread of the layer costs: few rows are clamped everywhere).  Then the rows go through the
+    // list in passes, kRpw rows of every wave at a time, which always fit: each wave reads its
+    // own rows of the pass again (once per workgroup, not once per wave), appends the live ones,
+    // and every wave reduces that list.  Three counters take turns, so that the one a pass uses
+    // was cleared while the pass before it was under way and after its last reader had gone.
+    constexpr int kRpw = kKeep / NG;
+    static_assert(kRpw >= 1, "one pass holds at least one row of every wave");
+    int cnt = n > 0 ? uniform((int)count[0]) : 0;
+    int r_next = TS;                               // first row of the next pass; TS: no further pass
+    if (cnt > kKeep) {
+        r_next = 0;
+        cnt = -1;                                  // nothing to reduce yet
     }
-    if (nsurv > 0) {
-        const bool pruned = nsurv <= kKeep;        // workgroup-uniform
-        const int nrow = pruned ? nsurv : n;
-        const int npair = (nrow + 1) / 2;          // an odd tail repeats its entry: min(x, x) = x
-        Cell va[2][TE], vb[2][TE];
-        int spa[2], spb[2];
-        R32Row<TS> ra[2], rb[2];
-        auto request = [&](int q, int pr) {
-            const int ia = 2 * pr < nrow ? 2 * pr : nrow - 1;
-            const int ib = 2 * pr + 1 < nrow ? 2 * pr + 1 : nrow - 1;
-            if (pruned) {
+    uint32_t rows_reduced = 0;
+    int pass = 0;
+    for (;;) {
+        if (cnt < 0) {                             // workgroup-uniform
+            ++pass;
+            uint32_t *counter = count + (pass % 3 == 2 ? 3 : pass % 3);
+            if (g == 0 && lane == 0) count[(pass + 1) % 3 == 2 ? 3 : (pass + 1) % 3] = 0;
+#pragma unroll
+            for (int r = 0; r < TS; ++r)
+                if (r >= r_next && r < r_next + kRpw && (keep >> r & 1)) {
+                    Cell cells[TE];
+                    load_row(read_lane(my_ent, r), read_lane(my_c0, r), cells);
+                    append_row(r, cells, counter);
+                }
+            __syncthreads();
+            cnt = uniform((int)counter[0]);        // at most NG * kRpw = kKeep
+            r_next += kRpw;
+        }
+        rows_reduced += (uint32_t)cnt;
+        if (s0 < S && cnt > 0) {                   // (an idle strategy group only contributes its rows)
+            const int npair = (cnt + 1) / 2;       // an odd tail repeats its entry: min(x, x) = x
+            uint32_t va[2][TE], vb[2][TE];
+            int spa[2], spb[2];
+            R32Row<TS> ra[2], rb[2];
+            auto request = [&](int q, int pr) {
+                const int ia = 2 * pr < cnt ? 2 * pr : cnt - 1;
+                const int ib = 2 * pr + 1 < cnt ? 2 * pr + 1 : cnt - 1;
                 spa[q] = uniform((int)meta[ia]);
                 spb[q] = uniform((int)meta[ib]);
 #pragma unroll
@@ -1375,45 +1395,43 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
                     va[q][j] = keys[ia * kCols + j * kWave + lane];
                     vb[q][j] = keys[ib * kCols + j * kWave + lane];
                 }
-            } else {
-                const uint64_t ea = vl[ia], eb = vl[ib];
-                spa[q] = uniform((int)(uint32_t)ea);     // (scalars already; said so for the compiler, which
-                spb[q] = uniform((int)(uint32_t)eb);     // merges them with the other branch's values)
-                load_row(ea, (Cell)vc[ia], va[q]);
-                load_row(eb, (Cell)vc[ib], vb[q]);
-            }
-        };
-        auto reduce_pair = [&](int q) {
-            // keys of the next pair's rows, in flight under this pair's arithmetic
-            ra[q ^ 1].request(Rk + (int64_t)uniform(spa[q ^ 1]) * a.S_pad);
-            rb[q ^ 1].request(Rk + (int64_t)uniform(spb[q ^ 1]) * a.S_pad);
-            uint32_t da[TE], db[TE];
+            };
+            auto reduce_pair = [&](int q) {
+                // keys of the next pair's rows, in flight under this pair's arithmetic
+                ra[q ^ 1].request(Rk + (int64_t)uniform(spa[q ^ 1]) * a.S_pad);
+                rb[q ^ 1].request(Rk + (int64_t)uniform(spb[q ^ 1]) * a.S_pad);
 #pragma unroll
-            for (int j = 0; j < TE; ++j) {         // kept rows are keys already; others are raw cells
-                const uint32_t ka = (uint32_t)min((Cell)(va[q][j] - cmin[j]), (Cell)dmax) << k;
-                const uint32_t kb = (uint32_t)min((Cell)(vb[q][j] - cmin[j]), (Cell)dmax) << k;
-                da[j] = pruned ? (uint32_t)va[q][j] : ka;
-                db[j] = pruned ? (uint32_t)vb[q][j] : kb;
+                for (int s = 0; s < TS; ++s)
+                    minplus_u32x2<TE>(acc[s], va[q], vb[q], ra[q].at(s), rb[q].at(s), ra[q ^ 1], rb[q ^ 1]);
+                r32_await(ra[q ^ 1], rb[q ^ 1]);
+            };
+            request(0, 0);
+            request(1, 1);
+            ra[0].request(Rk + (int64_t)uniform(spa[0]) * a.S_pad);
+            rb[0].request(Rk + (int64_t)uniform(spb[0]) * a.S_pad);
+            r32_await(ra[0], rb[0]);
+            int pr = 0;
+            for (; pr + 2 <= npair; pr += 2) {
+                reduce_pair(0);
+                request(0, pr + 2);
+                reduce_pair(1);
+                request(1, pr + 3);
             }
-#pragma unroll
-            for (int s = 0; s < TS; ++s)
-                minplus_u32x2<TE>(acc[s], da, db, ra[q].at(s), rb[q].at(s), ra[q ^ 1], rb[q ^ 1]);
-            r32_await(ra[q ^ 1], rb[q ^ 1]);
-        };
-        request(0, 0);
-        request(1, 1);
-        ra[0].request(Rk + (int64_t)uniform(spa[0]) * a.S_pad);
-        rb[0].request(Rk + (int64_t)uniform(spb[0]) * a.S_pad);
-        r32_await(ra[0], rb[0]);
-        int pr = 0;
-        for (; pr + 2 <= npair; pr += 2) {
-            reduce_pair(0);
-            request(0, pr + 2);
-            reduce_pair(1);
-            request(1, pr + 3);
+            if (pr < npair) reduce_pair(0);
         }
-        if (pr < npair) reduce_pair(0);
+        if (r_next >= TS) break;
+        __syncthreads();                           // the list is free again
+        cnt = -1;
     }
+    if (g == 0 && lane == 0) {                     // statistics: how much the pruning removed
+        uint32_t *st = a.stats + 2 * (((int64_t)b * (a.L - 1) + (l - 1)) * a.n_tiles +
+                                      (uint32_t)tile_start / (uint32_t)a.tile_e);
+        const uint32_t rows = rows_reduced << 16 | (uint32_t)n;
+        const uint32_t fetched = n > 0 ? count[2] : 0u;
+        st[0] = add_stats ? st[0] + rows : rows;   // (a tile swept in several parts adds them up)
+        st[1] = add_stats ? st[1] + fetched : fetched;
+    }
+    if (s0 >= S) return;                           // an idle strategy group has done its share of the rows
 
     const uint32_t mask = (1u << k) - 1u;
 #pragma unroll
