@@ -31,6 +31,10 @@
 //    of layer costs some 90-95 % of the candidates fall away and the sweep is bound by HBM.
 //    The keys' width depends on the transition costs only; when the costs themselves outgrow
 //    32-bit cells, the same body runs over 64-bit cells (up to 256 strategies).
+//    Where a layer fills the chip, these instances keep a SINGLE table: the reduced key of a
+//    state, (cost relative to its column's former minimum) * 2^k + argmin, is what the
+//    back-pointer's 32-bit word stores, with one former minimum per budget column beside it;
+//    the next layer rebuilds the cells it reads, and no cost rows are written (half the bytes).
 //  * 64-bit keys: key = cost * 2^k + s' (k = ceil(log2 S)) lives in the mantissa of a double
 //    whose exponent is pinned, K = 2^52 + key; one v_add_f64 + one v_min_f64 per candidate,
 //    exact while K stays below 2^53.  Two storage widths: narrow (costs below 2^31 stored as
