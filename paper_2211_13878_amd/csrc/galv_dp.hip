@@ -2238,17 +2238,20 @@ galv_status_t galv_dp_create(const galv_dp_desc_t *desc, void *workspace_dev,
     h->n_side = 0;
     int n = (int)((desc->flags & GALV_DP_STREAMS_MASK) >> GALV_DP_STREAMS_SHIFT);
     if (n == 0) {
-        // Automatic, from the estimated duration of one layer's sweep when it streams its
-        // 12 bytes per state at ~5.5 TB/s (what the pruned 32-bit-key sweep reaches; the estimate
-        // is within 2x of the measured single-stream launches of 12, 33, 145 and 290 us on the
-        // four named shapes).  Measured on MI355X with 4 hardware queues: sweeps of 150-300 us
-        // gain 10-30 % from 9 streams (5-7 are nearly as good; multiples of 4 gain little),
-        // sweeps of tens of microseconds gain ~10 % from 2 and lose with more (host launch
-        // rate), shorter ones lose with any, and sweeps near a millisecond or longer gain
-        // ~5 % from 2 (or 5) and less from 9.
+        // Automatic, from the estimated duration of one layer's sweep when it streams 12 bytes
+        // per state at ~5.5 TB/s (within 2x of the measured single-stream launches of 11, 26, 105
+        // and 220 us on the four named shapes).  Measured on MI355X with 4 hardware queues:
+        // sweeps of 100 us and more gain 10-30 % from 8-10 streams (more than 10 lose again when
+        // a stream's launches get short: the launch rate binds) and still a few per cent when a
+        // launch takes a millisecond; sweeps of tens of microseconds gain ~10 % from 2 and lose
+        // with more; shorter ones lose with any.  A stream that holds two instances where
+        // others hold one sets the pace, so a batch of up to 16 large instances gets one
+        // stream per instance (16 instances of 128 strategies x 65536 columns: 22.1 ms with 16
+        // streams, 24.6 with 12, 25.3 with 9).
         const double us = 12.0 * desc->n_instances * ((double)desc->max_budget + 1) *
                           desc->n_strategies / 5.5e12 * 1e6;
-        n = us < 20.0 ? 1 : (us < 100.0 ? 2 : (us < 600.0 ? 9 : 2));
+        n = us < 20.0 ? 1 : (us < 100.0 ? 2 : 9);
+        if (n == 9 && desc->n_instances <= kMaxSide && us / desc->n_instances >= 12.0) n = desc->n_instances;
     }
     if (n > desc->n_instances) n = desc->n_instances;
     if (n > 1 && desc->n_layers > 1) {
