@@ -78,8 +78,10 @@ typedef struct {
                                   an instance's values would allow the faster exact path */
 #define GALV_DP_BP_U8 2u       /* keep back-pointers in one byte instead of four (internal
                                   storage only: results are identical); needs n_strategies <= 255.
-                                  Shrinks the largest table of the workspace and the dominant
-                                  HBM write of the sweep by 4x */
+                                  Shrinks the largest table of the workspace by 4x.  The sweep
+                                  then keeps rolling cost rows (9 bytes per state); where the
+                                  single packed table applies (GALV_DP_FORCE_PACK) that form is
+                                  the faster one, and this flag buys memory, not time */
 
 #define GALV_DP_NO_U32 4u      /* do not use the 32-bit integer-key kernels (see
                                   GALV_INSTANCE_OK_FAST_U32); the 64-bit-key ones take over   */
