@@ -111,6 +111,7 @@ inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // running minima per lane, NG strategy groups per workgroup.
 struct Variant {
     int ts, te, ng, w, ux; // w: wavefronts per workgroup (w / ng budget sub-tiles); ux: see sweep_kernel
+    int wpe;               // waves per SIMD the kernel is built for
     int share;             // 1: the row-sharing 32-bit-key body (one tile per workgroup, LDS for the kept rows)
 };
 
@@ -1060,7 +1061,20 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int wave, int l, int 
 
 // How many surviving rows the row-sharing body below keeps in LDS for a workgroup that covers
 // `cap` strategies (host and device agree through this one function).
-constexpr int keep_rows(int cap) { return cap <= 64 ? 16 : 32; }
+// As many as the LDS holds without costing a resident workgroup: a CU holds wpe * 4 / ng
+// workgroups by registers, each may take that share of the 160 KB (at most the 64 KB a kernel
+// gets without asking); what the partial minima and counters leave goes to the list, in whole
+// rows per wave and pass.  8, 11, 16, 22, 32, 48, 96 and 96 rows for the eight variants below:
+// all rows up to 8 strategies, three quarters of them at 44 and 128.
+constexpr int keep_rows(int ts, int ng, int wpe) {
+    const int wgs = wpe * 4 / ng > 0 ? wpe * 4 / ng : 1;
+    const int share = 160 * 1024 / wgs < 64 * 1024 ? 160 * 1024 / wgs : 64 * 1024;
+    const int fixed = ng * 128 * 4 + ng * 8 + 16 + 256;
+    int rows = (share - fixed) / (128 * 4 + 4);
+    if (rows > ts * ng) rows = ts * ng;
+    rows -= rows % ng;
+    return rows < ng ? ng : rows;
+}
 
 // Row-sharing form of the 32-bit-key body, for S <= TS * NG (up to 256) with one budget tile of
 // 64 * TE columns per workgroup of NG waves.  Wave g owns the former-layer rows g, g + NG, ...
@@ -1076,10 +1090,11 @@ constexpr int keep_rows(int cap) { return cap <= 64 ? 16 : 32; }
 //      tie-break rides in the low bits of the keys.
 //   3. The inner loop runs over the surviving rows only, reading keys from LDS and R keys by
 //      scalar loads.  Should more rows survive than the list holds (transition costs that dwarf
-//      the spread of the layer costs), the workgroup falls back to the full loop over all usable
-//      rows, read again through the caches and turned into keys on the fly.
-// Only the survivors' keys live in LDS (keep_rows rows instead of S), which is what lets four
-// 8-wave workgroups share a CU at S = 128.
+//      the spread of the layer costs), the rows go through the list in passes, a few rows of
+//      every wave at a time: each wave reads its rows of the pass again, appends the live ones,
+//      and every wave reduces that list.
+// Only the survivors' keys live in LDS, as many rows as fit without costing a resident workgroup
+// (keep_rows), which is what lets three 8-wave workgroups share a CU at S = 128.
 //
 // PACK: the table of back-pointers is the ONLY table.  The reduced key of a state already holds
 // both results, (cost relative to the column's former minimum Cmin) << k | argmin, and
@@ -1088,7 +1103,7 @@ constexpr int keep_rows(int cap) { return cap <= 64 ? 16 : 32; }
 // per budget column beside it (rolling, in the space of the cost rows, which it replaces), and
 // the next layer rebuilds the cells of the rows it fetches: 4 bytes written and at most 4 read
 // per state instead of 8 and 4.  The backtrack masks the index out of the word.
-template <int TS, int TE, int NG, class BP, class Cell, bool PACK>
+template <int TS, int TE, int NG, class BP, class Cell, bool PACK, int KEEP>
 __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, int b, int budget,
                                                  int64_t tile_start, bool add_stats, int n, uint32_t dmax,
                                                  int r_sel, uint64_t my_ent, uint64_t my_c0_64) {
@@ -1109,7 +1124,7 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
     constexpr Cell kAllOnes = ~(Cell)0;
     static_assert(TS <= 16, "one scalar load fetches the R keys of a row");
     constexpr int kCols = kWave * TE;
-    constexpr int kKeep = keep_rows(TS * NG);
+    constexpr int kKeep = KEEP;                    // rows the list holds (keep_rows of the variant)
     (void)budget;
     const int lane = lane_id();                    // (g: the wave = owner of rows g + NG * r = strategy group)
     const int64_t e0 = tile_start + lane;
@@ -1513,7 +1528,7 @@ __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) 
     if (tile_start > budget) return;
     if (st == GALV_INSTANCE_OK_FAST_U32) {
         if constexpr (SHARE)
-            sweep_u32_shared<TS, TE * UX, NG, BP, uint32_t, PACK != 0>(a, wave, l, b, budget, tile_start, false, n_prev, dmax, r_sel, my_ent, my_c0);
+            sweep_u32_shared<TS, TE * UX, NG, BP, uint32_t, PACK != 0, keep_rows(TS, NG, WPE)>(a, wave, l, b, budget, tile_start, false, n_prev, dmax, r_sel, my_ent, my_c0);
         else
             sweep_u32<TS, TE * UX, NG, BP>(a, wave, l, b, budget, tile_start);
     } else if (st == GALV_INSTANCE_OK_U32_WIDE) {
@@ -1523,7 +1538,7 @@ __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) 
             for (int h = 0; h < TE * UX; ++h) {
                 if (tile_start + h * kWave > budget) break;          // workgroup-uniform
                 if (h) __syncthreads();                              // the LDS of the part before is free again
-                sweep_u32_shared<TS, 1, NG, BP, uint64_t, PACK != 0>(a, wave, l, b, budget, tile_start + h * kWave, h > 0, n_prev, dmax, r_sel, my_ent, my_c0);
+                sweep_u32_shared<TS, 1, NG, BP, uint64_t, PACK != 0, keep_rows(TS, NG, WPE)>(a, wave, l, b, budget, tile_start + h * kWave, h > 0, n_prev, dmax, r_sel, my_ent, my_c0);
             }
         }
     } else if (st == GALV_INSTANCE_OK_FAST) {
@@ -1932,7 +1947,7 @@ VariantEntry variant_entry() {
     static_assert((UX == 1 || UX == 2) && TE * UX <= 4, "budget columns per lane");
     SweepFn pack = nullptr;
     if constexpr (SHARE != 0) pack = sweep_kernel<TS, TE, NG, WPE, int32_t, W, UX, SHARE, 1>;
-    return {{TS, TE, NG, W, UX, SHARE},
+    return {{TS, TE, NG, W, UX, WPE, SHARE},
             sweep_kernel<TS, TE, NG, WPE, int32_t, W, UX, SHARE, 0>,
             sweep_kernel<TS, TE, NG, WPE, uint8_t, W, UX, SHARE, 0>,
             pack};
@@ -2025,7 +2040,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     // row-sharing body: partial minima [NG][columns], counters, keep_rows rows of (strategy index, keys), [NG] minima
     p->lds_bytes = 0;
     if (v.share) {
-        const size_t cols = (size_t)kWave * v.te * v.ux, keep = keep_rows(v.ts * v.ng);
+        const size_t cols = (size_t)kWave * v.te * v.ux, keep = keep_rows(v.ts, v.ng, v.wpe);
         const size_t narrow = ((size_t)v.ng * cols + v.ng + 4 + keep + keep * cols) * sizeof(uint32_t);
         // the 8-byte-cell form works on 64 columns at a time
         const size_t wide = ((size_t)v.ng * kWave + v.ng) * sizeof(uint64_t) + (4 + keep + keep * kWave) * sizeof(uint32_t);
