@@ -416,6 +416,23 @@ def test_path_limits_by_transition_cost():
                             binding.GALV_INSTANCE_OK_FAST_U32]
 
 
+@pytest.mark.parametrize("L,expect", [(3, binding.GALV_INSTANCE_OK_FAST_U32), (6, binding.GALV_INSTANCE_OK_U32_WIDE)])
+def test_largest_possible_key_is_a_candidate_but_never_a_stored_word(L, expect):
+    """S = 16 (four index bits) and the largest R the 32-bit keys allow, 2^27 - 1: a former
+    strategy 15 that is clamped (relative cost R_max + 1) and pays R_max yields the key 2^32 - 1,
+    the very pattern the packed table uses for "unreachable".  It can never win (the strategy
+    that attains the column's minimum offers a smaller key), so tables and plans must come out
+    the same in both table forms."""
+    rmax = (1 << 27) - 1
+    w = workloads.random_workload(91, 2, L, 16, 500, nR=1, m_range=(0, 120), c_range=(0, 1000),
+                                  r_range=(0, rmax), infeasible=0.05, zero_diagonal=False)
+    w.R[:, 0, 15, :] = rmax                       # strategy 15 always pays the largest transition cost
+    w.c[:, :, 15] += 2 * (1 << 27)                # ... and costs so much that it is clamped wherever another strategy fits
+    w.budget[:] = [500, 377]
+    for flags in (binding.GALV_DP_FORCE_PACK, binding.GALV_DP_NO_PACK, binding.GALV_DP_FORCE_PACK | binding.GALV_DP_FORCE_PEEK):
+        check_against_oracle(w, flags=flags, table_instances=[0, 1], expect_status=expect)
+
+
 def test_bad_values_are_reported_not_solved():
     w = workloads.random_workload(3, 5, 4, 5, 50, m_range=(0, 9), c_range=(0, 9), r_range=(0, 9))
     w.c[0, 1, 2] = -1
