@@ -126,7 +126,7 @@ struct Layout {
     int64_t row;          // cells per cost row: lead + padded columns (8 bytes reserved each)
     int64_t e_pad;        // padded budget columns (multiple of kEAlign)
     char *U[2];           // rolling cost rows   [B][S_pad][row] of 8-byte slots
-    void *bp;             // argmin, un-shifted  [B][L-1][e_pad / 128][S][128] of int32, or of uint8 (0xFF = none)
+    void *bp;             // argmin, un-shifted  [B][L-1][S][e_pad] of int32, or of uint8 (0xFF = none)
     int32_t bp_u8;        // 1: one-byte back-pointers
     int32_t peek;         // 1: the row-sharing sweep looks at two cells of a row before it fetches the row
     int32_t packed;       // 1: instances on the 32-bit-key paths keep ONE table: the back-pointer word holds the
@@ -191,18 +191,6 @@ __device__ __forceinline__ int lead_kind(int st) {
     if (st == GALV_INSTANCE_OK_FAST_WIDE) return 2;
     if (st == GALV_INSTANCE_OK_U32_WIDE) return 3;
     return 0;
-}
-
-// The back-pointer table of one (instance, layer) is laid out in blocks of kBlk budget columns x
-// all strategies, [e_pad / kBlk][S][kBlk]: what a workgroup writes for its tile is then one
-// contiguous piece of memory (S x 512 bytes) instead of S pieces a whole row apart, and the
-// shifted row segments the next layer reads for a tile come from a few neighbouring blocks.
-constexpr int kBlk = 128;
-__device__ __forceinline__ int64_t bp_layer(const Layout &a, int b, int l) {      // first element of layer l >= 1
-    return ((int64_t)b * (a.L - 1) + (l - 1)) * a.S * a.e_pad;
-}
-__device__ __forceinline__ int64_t bp_cell(const Layout &a, int64_t s, int64_t e) {   // (s, e) within its layer
-    return ((e >> 7) * a.S + s) * kBlk + (e & (kBlk - 1));
 }
 
 // Whether instance status st keeps the single packed table (a handle-wide choice of kernels, and
@@ -583,7 +571,7 @@ __device__ __forceinline__ void sweep_int64(const Layout &a, int wave, int l, in
                 if (s0 + q < S) {
                     const bool dead = best[q] >= kInf;
                     Unew[(s0 + q) * a.row + e] = dead ? kInf : best[q] + cl[s0 + q];
-                    store_bp(a, bp0 + bp_cell(a, s0 + q, e), dead ? -1 : arg[q]);
+                    store_bp(a, bp0 + (s0 + q) * a.e_pad + e, dead ? -1 : arg[q]);
                 }
             }
         }
@@ -703,7 +691,7 @@ __device__ __forceinline__ void sweep_fast_at(const Layout &a, int l, int b, int
                      (int64_t)b * a.S_pad * pitch + a.lead + (e0 - lane);
     Cell *Un = reinterpret_cast<Cell *>(a.U[l & 1]) + ((int64_t)b * a.S_pad + s0) * pitch +
                a.lead + e0;
-    BP *bp = static_cast<BP *>(a.bp) + bp_layer(a, b, l);
+    BP *bp = static_cast<BP *>(a.bp) + (((int64_t)b * (a.L - 1) + (l - 1)) * S + s0) * a.e_pad + e0;
     const int r = a.r_idx ? a.r_idx[(int64_t)b * a.L + l] : 0;
     const ConstPtr<double> Rk = as_const(a.Rk + ((int64_t)b * a.nR + r) * S * a.S_pad + s0);
     const ConstPtr<uint64_t> ck = as_const(a.ck + ((int64_t)b * a.L + l) * a.S_pad + s0);
@@ -794,7 +782,7 @@ __device__ __forceinline__ void sweep_fast_at(const Layout &a, int l, int b, int
                 // Back-pointers are written once and read again only by the backtrack: a
                 // streaming store keeps them from pushing the cost rows, which the next
                 // layer reads back, out of the caches.  (-1 becomes 0xFF in one byte.)
-                __builtin_nontemporal_store((BP)arg, &bp[bp_cell(a, s0 + s, e_wave + j * kWave) + lane]);
+                __builtin_nontemporal_store((BP)arg, &bp[(int64_t)s * a.e_pad + j * kWave]);
             }
         }
     }
@@ -937,8 +925,7 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int wave, int l, int 
                          (int64_t)b * a.S_pad * pitch + a.lead + (e0 - lane);
     uint32_t *Un = reinterpret_cast<uint32_t *>(a.U[l & 1]) + ((int64_t)b * a.S_pad + s0) * pitch +
                    a.lead + e0;
-    BP *bp = static_cast<BP *>(a.bp) + bp_layer(a, b, l);
-    const int64_t e_wave = tile_start + (int64_t)esub * (kWave * TE);      // this wave's first column
+    BP *bp = static_cast<BP *>(a.bp) + (((int64_t)b * (a.L - 1) + (l - 1)) * S + s0) * a.e_pad + e0;
     const int r = a.r_idx ? a.r_idx[(int64_t)b * a.L + l] : 0;
     const ConstPtr<uint32_t> Rk =
         as_const(reinterpret_cast<const uint32_t *>(a.Rk + ((int64_t)b * a.nR + r) * S * a.S_pad) + s0);
@@ -1066,7 +1053,7 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int wave, int l, int 
                 // streaming store keeps them from pushing the cost rows, which the next
                 // layer reads back, out of the caches.  (-1 becomes 0xFF in one byte.)
                 __builtin_nontemporal_store((BP)(alive ? (int32_t)(key & mask) : -1),
-                                            &bp[bp_cell(a, s0 + s, e_wave + j * kWave) + lane]);
+                                            &bp[(int64_t)s * a.e_pad + j * kWave]);
             }
         }
     }
@@ -1151,13 +1138,14 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
     // (wave-uniform: the first column of the tile in this wave's first output row)
     Cell *Un_tile = reinterpret_cast<Cell *>(a.U[l & 1]) + ((int64_t)b * a.S_pad + s0) * pitch +
                     a.lead + tile_start;
-    BP *bp_tile = static_cast<BP *>(a.bp) + bp_layer(a, b, l) + bp_cell(a, s0, tile_start);
+    BP *bp_tile = static_cast<BP *>(a.bp) + (((int64_t)b * (a.L - 1) + (l - 1)) * S + s0) * a.e_pad + tile_start;
     const ConstPtr<uint32_t> Rk =
         as_const(reinterpret_cast<const uint32_t *>(a.Rk + ((int64_t)b * a.nR + r_sel) * S * a.S_pad) + s0);
     const ConstPtr<uint64_t> ck = as_const(a.ck + ((int64_t)b * a.L + l) * a.S_pad + s0);
-    // PACK: the former layer's words (no lead: a column below the shift is tested for instead)
-    // and column minima, and this layer's column minima
-    const uint32_t *Wp = static_cast<const uint32_t *>(a.bp) + bp_layer(a, b, l >= 2 ? l - 1 : 1);
+    // PACK: the former layer's words (rows of e_pad, no lead: a column below the shift is tested
+    // for instead) and column minima, and this layer's column minima
+    const uint32_t *Wp = static_cast<const uint32_t *>(a.bp) +
+                         ((int64_t)b * (a.L - 1) + (l >= 2 ? l - 2 : 0)) * S * a.e_pad;
     const Cell *Mp = reinterpret_cast<const Cell *>(a.U[(l - 1) & 1] + (int64_t)b * a.S_pad * a.row * 8);
     Cell *Mn_tile = reinterpret_cast<Cell *>(a.U[l & 1] + (int64_t)b * a.S_pad * a.row * 8) + tile_start;
     const Cell my_c0 = (Cell)my_c0_64;
@@ -1173,6 +1161,7 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
 #pragma unroll
             for (int j = 0; j < TE; ++j) out[j] = e0 + j * kWave >= (int64_t)shift ? cp : kInfCell;
         } else if constexpr (PACK) {
+            const uint32_t *w = Wp + (int64_t)sp * a.e_pad;
             uint32_t wv[TE];
             Cell mv[TE];
             bool ok[TE];
@@ -1181,7 +1170,7 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
                 const int64_t idx = e0 + j * kWave - (int64_t)shift;
                 ok[j] = idx >= 0;
                 const uint32_t x = ok[j] ? (uint32_t)idx : 0u;       // idx < e_pad <= 2^31 + 1024
-                wv[j] = Wp[bp_cell(a, sp, x)];
+                wv[j] = w[x];
                 mv[j] = Mp[x];
             }
 #pragma unroll
@@ -1247,7 +1236,7 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
         } else if constexpr (PACK) {
             const bool ok = idx >= 0;
             const uint32_t x = ok ? (uint32_t)idx : 0u;
-            const uint32_t wv = Wp[bp_cell(a, my_sp, x)];
+            const uint32_t wv = Wp[(int64_t)my_sp * a.e_pad + x];
             const Cell mv = Mp[x];
             const Cell cell = mv + (Cell)(wv >> k) + my_c0;
             mine = ok && wv != 0xffffffffu ? cell : kInfCell;
@@ -1292,12 +1281,12 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
                     if (r >= TS) break;
                     if (keep >> r & 1) {
                         const uint64_t e_r = read_lane(my_ent, r);
-                        const uint32_t sp_r = (uint32_t)e_r;
+                        const uint32_t *w = Wp + (int64_t)(uint32_t)e_r * a.e_pad;
 #pragma unroll
                         for (int j = 0; j < TE; ++j) {
                             const int64_t idx = e0 + j * kWave - (int64_t)(uint32_t)(e_r >> 32);
                             const uint32_t x = idx >= 0 ? (uint32_t)idx : 0u;
-                            const uint32_t v = Wp[bp_cell(a, sp_r, x)];
+                            const uint32_t v = w[x];
                             wv[q][j] = idx >= 0 ? v : 0xffffffffu;
                             mv[q][j] = Mp[x];
                         }
@@ -1473,7 +1462,7 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
                 const bool alive = cmin[j] < kInfCell;
                 const uint32_t key = acc[s][j];
                 // (wave-uniform row address + the lane's offset: no per-store address arithmetic)
-                BP *bp_row = bp_tile + s * kBlk;     // (the tile's block, or its half of it, of row s0 + s)
+                BP *bp_row = bp_tile + (int64_t)s * a.e_pad;
                 if constexpr (PACK) {
                     // (a winning key is never all ones: the winner's relative cost is not clamped)
                     bp_row[(uint32_t)lane + j * kWave] = (BP)(alive ? key : 0xffffffffu);
@@ -1573,7 +1562,7 @@ __device__ __forceinline__ int64_t last_layer_cost(const Layout &a, int b, int s
     if (is_packed(a, st)) {
         // U_{L-1}[e'][s] = Cmin[e'] + (key >> k) + c(L-1, s) with e' = e - shift
         const int64_t x = e - shift;
-        const uint32_t w = static_cast<const uint32_t *>(a.bp)[bp_layer(a, b, a.L - 1) + bp_cell(a, s, x)];
+        const uint32_t w = static_cast<const uint32_t *>(a.bp)[(((int64_t)b * (a.L - 1) + (a.L - 2)) * a.S + s) * a.e_pad + x];
         if (w == 0xffffffffu) return kInf;
         const char *M = a.U[(a.L - 1) & 1] + (int64_t)b * a.S_pad * a.row * 8;
         const int64_t cmin = st == GALV_INSTANCE_OK_U32_WIDE ? (int64_t)reinterpret_cast<const uint64_t *>(M)[x]
@@ -1639,7 +1628,7 @@ __device__ __forceinline__ void walk_plan(const Layout &a, int b, int64_t e, int
             for (int q = 0; q < a.L; ++q) out[q] = -1;
             return;
         }
-        s = load_bp(a, st, bp_layer(a, b, l) + bp_cell(a, s, e));
+        s = load_bp(a, st, (((int64_t)b * (a.L - 1) + (l - 1)) * a.S + s) * a.e_pad + e);
         if (s < 0 || s >= a.S) {
             for (int q = 0; q < a.L; ++q) out[q] = -1;
             return;
@@ -1706,7 +1695,7 @@ __global__ __launch_bounds__(kWave) void backtrack_kernel(Layout a, int32_t *pla
             for (int q = 0; q < a.L; ++q) out[q] = -1;
             return;
         }
-        s = load_bp(a, st, bp_layer(a, b, l) + bp_cell(a, s, e));
+        s = load_bp(a, st, (((int64_t)b * (a.L - 1) + (l - 1)) * a.S + s) * a.e_pad + e);
         if (s < 0 || s >= a.S) {
             for (int q = 0; q < a.L; ++q) out[q] = -1;
             return;
@@ -1783,7 +1772,7 @@ __global__ __launch_bounds__(kThreads) void export_kernel(Layout a, int b, int64
         if (live && l >= 1) {
             const int64_t shift = a.m[((int64_t)b * a.L + l) * a.S + s];
             if (shift <= e)
-                v = load_bp(a, st, bp_layer(a, b, l) + bp_cell(a, s, e - shift));
+                v = load_bp(a, st, (((int64_t)b * (a.L - 1) + (l - 1)) * a.S + s) * a.e_pad + (e - shift));
         }
         dst[s] = v;
     }
