@@ -130,6 +130,7 @@ def main():
     ap.add_argument("--no-pack", action="store_true",
                     help="rolling cost rows and plain back-pointers instead of the single packed table (GALV_DP_NO_PACK)")
     ap.add_argument("--force-pack", action="store_true", help="the single packed table whatever the shape (GALV_DP_FORCE_PACK)")
+    ap.add_argument("--no-wide-tiles", action="store_true", help="128-column tiles whatever the shape (GALV_DP_NO_WIDE_TILES)")
     ap.add_argument("--bp-u8", action="store_true",
                     help="store back-pointers in one byte (GALV_DP_BP_U8): 9 instead of 12 B per state")
     ap.add_argument("--streams", type=int, default=0,
@@ -267,6 +268,7 @@ def run_config(cfg, args, torch, binding, workloads):
                   (binding.GALV_DP_NO_U32 if args.no_u32 else 0) |
                   (binding.GALV_DP_NO_PACK if args.no_pack else 0) |
                   (binding.GALV_DP_FORCE_PACK if args.force_pack else 0) |
+                  (binding.GALV_DP_NO_WIDE_TILES if args.no_wide_tiles else 0) |
                   (binding.GALV_DP_BP_U8 if args.bp_u8 else 0))
     dev = binding.upload(w)
     torch.cuda.synchronize()
@@ -413,6 +415,7 @@ def run_config(cfg, args, torch, binding, workloads):
                    "single_packed_table": bool(packed and any(int(st) in (3, 4) for st in status)),
                    "internal_streams": main_leg["streams"],
                    "peek_before_fetch": bool(main_leg["peek"]),
+                   "tile_columns": main_leg["tile_columns"],
                    "hip_graph_replay": bool(args.graph),
                    "cell_updates_per_batch": nominal, "exact_candidates_per_batch": exact,
                    "table_states_per_batch": states},

@@ -102,6 +102,11 @@ typedef struct {
                                   Half the bytes per state.  By default this is done when a layer has
                                   enough workgroups to fill the chip (as for GALV_DP_FORCE_PEEK).
                                   Results, exported tables included, are identical either way.       */
+#define GALV_DP_FORCE_WIDE_TILES 128u   /* sweep workgroups take tiles of 256 budget columns instead of 128
+                                           (22, 44 and 128 strategies' kernel variants have such a twin).
+                                           By default this is done when a layer has enough workgroups to
+                                           fill the chip, as for GALV_DP_FORCE_PEEK.  Results are identical. */
+#define GALV_DP_NO_WIDE_TILES 0x2000u   /* always 128-column tiles                                           */
 #define GALV_DP_STREAMS_SHIFT 8 /* bits 8..12: how many internal streams the layer sweeps are   */
 #define GALV_DP_STREAMS_MASK 0x1f00u /* spread over; 0 = chosen from the shape, 1 = none, at most 16 */
 #define GALV_DP_STREAMS(n) ((uint32_t)(n) << GALV_DP_STREAMS_SHIFT)

@@ -28,6 +28,8 @@ GALV_DP_NO_PEEK = 8
 GALV_DP_FORCE_PEEK = 16
 GALV_DP_NO_PACK = 32
 GALV_DP_FORCE_PACK = 64
+GALV_DP_FORCE_WIDE_TILES = 128
+GALV_DP_NO_WIDE_TILES = 0x2000
 
 
 def GALV_DP_STREAMS(n: int) -> int:

@@ -1066,11 +1066,11 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int wave, int l, int 
 // gets without asking); what the partial minima and counters leave goes to the list, in whole
 // rows per wave and pass.  8, 11, 16, 22, 32, 48, 96 and 96 rows for the eight variants below:
 // all rows up to 8 strategies, three quarters of them at 44 and 128.
-constexpr int keep_rows(int ts, int ng, int wpe) {
+constexpr int keep_rows(int ts, int ng, int wpe, int cols) {       // cols: budget columns of a tile
     const int wgs = wpe * 4 / ng > 0 ? wpe * 4 / ng : 1;
     const int share = 160 * 1024 / wgs < 64 * 1024 ? 160 * 1024 / wgs : 64 * 1024;
-    const int fixed = ng * 128 * 4 + ng * 8 + 16 + 256;
-    int rows = (share - fixed) / (128 * 4 + 4);
+    const int fixed = ng * cols * 4 + ng * 8 + 16 + 256;
+    int rows = (share - fixed) / (cols * 4 + 4);
     if (rows > ts * ng) rows = ts * ng;
     rows -= rows % ng;
     return rows < ng ? ng : rows;
@@ -1528,7 +1528,7 @@ __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) 
     if (tile_start > budget) return;
     if (st == GALV_INSTANCE_OK_FAST_U32) {
         if constexpr (SHARE)
-            sweep_u32_shared<TS, TE * UX, NG, BP, uint32_t, PACK != 0, keep_rows(TS, NG, WPE)>(a, wave, l, b, budget, tile_start, false, n_prev, dmax, r_sel, my_ent, my_c0);
+            sweep_u32_shared<TS, TE * UX, NG, BP, uint32_t, PACK != 0, keep_rows(TS, NG, WPE, kWave * TE * UX)>(a, wave, l, b, budget, tile_start, false, n_prev, dmax, r_sel, my_ent, my_c0);
         else
             sweep_u32<TS, TE * UX, NG, BP>(a, wave, l, b, budget, tile_start);
     } else if (st == GALV_INSTANCE_OK_U32_WIDE) {
@@ -1538,7 +1538,7 @@ __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) 
             for (int h = 0; h < TE * UX; ++h) {
                 if (tile_start + h * kWave > budget) break;          // workgroup-uniform
                 if (h) __syncthreads();                              // the LDS of the part before is free again
-                sweep_u32_shared<TS, 1, NG, BP, uint64_t, PACK != 0, keep_rows(TS, NG, WPE)>(a, wave, l, b, budget, tile_start + h * kWave, h > 0, n_prev, dmax, r_sel, my_ent, my_c0);
+                sweep_u32_shared<TS, 1, NG, BP, uint64_t, PACK != 0, keep_rows(TS, NG, WPE, kWave * TE * UX)>(a, wave, l, b, budget, tile_start + h * kWave, h > 0, n_prev, dmax, r_sel, my_ent, my_c0);
             }
         }
     } else if (st == GALV_INSTANCE_OK_FAST) {
@@ -1820,6 +1820,21 @@ __global__ __launch_bounds__(kThreads) void export_kernel(Layout a, int b, int64
 #ifndef GALV_V8
 #define GALV_V8 16, 2, 8, 6, 8, 1, 0
 #endif
+// Twins with tiles of 256 budget columns (UX = 2: four columns per lane) and fewer, fatter waves,
+// for launches that fill the chip anyway: what a tile costs beside its min-plus arithmetic (its
+// chain of round trips, its addresses and bookkeeping) is spread over twice the states.
+// Measured against the 128-column variants: 3.5 % (44 strategies x 32768 columns x 64 instances),
+// 5 % (128 x 65536 x 16), 2 % (22 x 24576 x 32); 3 % slower on 22 x 16384 x 8, which does not fill
+// the chip and keeps the narrow tiles.
+#ifndef GALV_V2X
+#define GALV_V2X 11, 2, 2, 5, 2, 2, 1
+#endif
+#ifndef GALV_V4X
+#define GALV_V4X 11, 2, 4, 5, 4, 2, 1
+#endif
+#ifndef GALV_V6X
+#define GALV_V6X 16, 2, 8, 4, 8, 2, 1
+#endif
 
 // ---------------------------------------------------------------------------------------------
 // Outer loop of Algorithm 1 over a window of batch sizes: per (batch size, pipeline degree) the
@@ -1953,14 +1968,22 @@ VariantEntry variant_entry() {
             pack};
 }
 
-const VariantEntry &pick_variant(int S) {
+// `wide_tiles`: the launch fills the chip; take the 256-column twin where there is one.
+const VariantEntry &pick_variant(int S, bool wide_tiles) {
     static const VariantEntry table[] = {
         variant_entry<GALV_V0>(), variant_entry<GALV_V1>(), variant_entry<GALV_V2>(),
         variant_entry<GALV_V3>(), variant_entry<GALV_V4>(), variant_entry<GALV_V5>(),
         variant_entry<GALV_V6>(), variant_entry<GALV_V7>(), variant_entry<GALV_V8>()};
+    static const VariantEntry twins[] = {
+        variant_entry<GALV_V2X>(), variant_entry<GALV_V4X>(), variant_entry<GALV_V6X>()};
     constexpr int n = sizeof table / sizeof table[0];
     for (int i = 0; i < n; ++i)
-        if (S <= table[i].v.ts * table[i].v.ng) return table[i];
+        if (S <= table[i].v.ts * table[i].v.ng) {
+            if (wide_tiles)
+                for (const VariantEntry &t : twins)
+                    if (t.v.ts == table[i].v.ts && t.v.ng == table[i].v.ng) return t;
+            return table[i];
+        }
     return table[n - 1];
 }
 
@@ -2006,7 +2029,8 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
         return fail(GALV_ERR_INVALID_ARG, "n_strategies %d exceeds the limit %d", d->n_strategies,
                     kMaxS);
     if (d->flags & ~(GALV_DP_FORCE_INT64 | GALV_DP_BP_U8 | GALV_DP_NO_U32 | GALV_DP_NO_PEEK | GALV_DP_FORCE_PEEK |
-                     GALV_DP_NO_PACK | GALV_DP_FORCE_PACK | GALV_DP_STREAMS_MASK))
+                     GALV_DP_NO_PACK | GALV_DP_FORCE_PACK | GALV_DP_FORCE_WIDE_TILES | GALV_DP_NO_WIDE_TILES |
+                     GALV_DP_STREAMS_MASK))
         return fail(GALV_ERR_INVALID_ARG, "unknown flag bits");
     if (((d->flags & GALV_DP_STREAMS_MASK) >> GALV_DP_STREAMS_SHIFT) > (uint32_t)kMaxSide)
         return fail(GALV_ERR_INVALID_ARG, "at most %d internal streams", kMaxSide);
@@ -2020,7 +2044,10 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
         return fail(GALV_ERR_RANGE, "max_budget %d exceeds 2^30", d->max_budget);
 
     memset(p, 0, sizeof *p);
-    const VariantEntry &ve = pick_variant(d->n_strategies);
+    // enough workgroups per layer to fill the chip several times over (counted in 128-column tiles)?
+    const bool fills_chip = ((int64_t)d->max_budget / 128 + 1) * d->n_instances >= 3072;
+    const bool wide_tiles = (fills_chip || (d->flags & GALV_DP_FORCE_WIDE_TILES)) && !(d->flags & GALV_DP_NO_WIDE_TILES);
+    const VariantEntry &ve = pick_variant(d->n_strategies, wide_tiles);
     const Variant v = ve.v;
     Layout &a = p->lay;
     a.B = d->n_instances;
@@ -2040,7 +2067,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     // row-sharing body: partial minima [NG][columns], counters, keep_rows rows of (strategy index, keys), [NG] minima
     p->lds_bytes = 0;
     if (v.share) {
-        const size_t cols = (size_t)kWave * v.te * v.ux, keep = keep_rows(v.ts, v.ng, v.wpe);
+        const size_t cols = (size_t)kWave * v.te * v.ux, keep = keep_rows(v.ts, v.ng, v.wpe, (int)cols);
         const size_t narrow = ((size_t)v.ng * cols + v.ng + 4 + keep + keep * cols) * sizeof(uint32_t);
         // the 8-byte-cell form works on 64 columns at a time
         const size_t wide = ((size_t)v.ng * kWave + v.ng) * sizeof(uint64_t) + (4 + keep + keep * kWave) * sizeof(uint32_t);
@@ -2051,7 +2078,6 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     a.e_pad = (int64_t)round_up((size_t)a.E_max + 1, kEAlign);
     a.n_tiles = (int32_t)((a.E_max + a.tile_e) / a.tile_e);   // ceil((E_max+1)/tile_e)
     // measured: with ~1000 workgroups per layer (config 1) the peek costs 9 %, with ~6000 (config 2) it gains 14 %
-    const bool fills_chip = (int64_t)a.n_tiles * a.B >= 3072;
     a.peek = fills_chip ? 1 : 0;
     if (d->flags & GALV_DP_NO_PEEK) a.peek = 0;
     if (d->flags & GALV_DP_FORCE_PEEK) a.peek = 1;

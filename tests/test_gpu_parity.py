@@ -301,7 +301,10 @@ def test_random_shapes_ragged_tiles(S):
                                   c_range=(0, 50), r_range=(0, 20), infeasible=0.08,
                                   zero_diagonal=False)
     w.budget[0] = E_max
-    for flags in ALL_PATHS + (binding.GALV_DP_FORCE_PEEK, binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_FORCE_PACK):
+    WIDE = binding.GALV_DP_FORCE_WIDE_TILES        # 256-column tiles (variants of 22, 44, 128 strategies)
+    for flags in ALL_PATHS + (binding.GALV_DP_FORCE_PEEK, binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_FORCE_PACK,
+                              WIDE | binding.GALV_DP_FORCE_PACK, WIDE | binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_FORCE_PACK,
+                              WIDE | binding.GALV_DP_NO_PACK, WIDE | binding.GALV_DP_NO_U32):
         check_against_oracle(w, flags=flags, table_instances=[0, 1, 2])
 
 
@@ -375,7 +378,7 @@ def test_large_costs_with_small_transition_costs_keep_32bit_keys(S):
     w.budget[:] = [700, 641, 577, 692]
     PACK, ROWS = binding.GALV_DP_FORCE_PACK, binding.GALV_DP_NO_PACK
     for peek in (binding.GALV_DP_FORCE_PEEK | PACK, binding.GALV_DP_NO_PEEK | PACK, binding.GALV_DP_FORCE_PEEK | ROWS,
-                 binding.GALV_DP_NO_PEEK | ROWS):
+                 binding.GALV_DP_NO_PEEK | ROWS, binding.GALV_DP_FORCE_PEEK | PACK | binding.GALV_DP_FORCE_WIDE_TILES):
         cost, _, _, status = check_against_oracle(w, flags=peek, table_instances=[0, 1, 3])
         assert list(status) == [binding.GALV_INSTANCE_OK_U32_WIDE] * 3 + [binding.GALV_INSTANCE_OK_FAST_U32]
         assert (cost[cost < INF] > (1 << 33)).any()

@@ -19,6 +19,7 @@ pytestmark = pytest.mark.gpu
 
 PEEK, NO_PEEK = binding.GALV_DP_FORCE_PEEK, binding.GALV_DP_NO_PEEK
 NO_PACK = binding.GALV_DP_NO_PACK          # rolling cost rows + plain back-pointers
+WIDE = binding.GALV_DP_FORCE_WIDE_TILES    # 256-column tiles where the variant has such a twin (22, 44, 128 strategies)
 PACK = binding.GALV_DP_FORCE_PACK          # the single packed table (these shapes are too small to choose it)
 
 
@@ -39,7 +40,7 @@ def test_nothing_can_be_pruned(S):
     w = workloads.random_workload(300 + S, 3, 5, S, 700, nR=2, m_range=(0, 150), c_range=(0, 9),
                                   r_range=(1000, 5000), infeasible=0.05, zero_diagonal=False)
     w.budget[0] = 700
-    for flags in (PEEK | PACK, NO_PEEK | PACK, PEEK | NO_PACK, NO_PEEK | NO_PACK):
+    for flags in (PEEK | PACK, NO_PEEK | PACK, PEEK | NO_PACK, NO_PEEK | NO_PACK, PEEK | PACK | WIDE, NO_PEEK | NO_PACK | WIDE):
         check_against_oracle(w, flags=flags, table_instances=[0, 1, 2], expect_status=binding.GALV_INSTANCE_OK_FAST_U32)
     st, _ = reduced_share(w, PEEK | PACK)
     assert (st[:, 1] > 0).all() and (st[:, 0] >= 0.85 * st[:, 1]).all()     # all but the tiles at the unreachable low budgets
@@ -54,7 +55,7 @@ def test_nearly_everything_is_pruned(S):
     w = workloads.random_workload(400 + S, 3, 6, S, 900, nR=2, m_range=(0, 120), c_range=(0, 100000),
                                   r_range=(0, 90), infeasible=0.05, zero_diagonal=False)
     w.budget[0] = 900
-    for flags in (PEEK | PACK, NO_PEEK | PACK, PEEK | NO_PACK, NO_PEEK | NO_PACK):
+    for flags in (PEEK | PACK, NO_PEEK | PACK, PEEK | NO_PACK, NO_PEEK | NO_PACK, PEEK | PACK | WIDE, NO_PEEK | NO_PACK | WIDE):
         check_against_oracle(w, flags=flags, table_instances=[0, 1, 2], expect_status=binding.GALV_INSTANCE_OK_FAST_U32)
     st, _ = reduced_share(w, NO_PEEK)
     assert (st[:, 2] == st[:, 1]).all()             # every listed row fetched
@@ -76,7 +77,7 @@ def test_mixtures_around_the_list_capacity(seed):
                                   r_range=(0, 400), infeasible=0.08, zero_diagonal=False)
     check_against_oracle(w, flags=PEEK | PACK, table_instances=[0, 1, 2])
     for flags in (NO_PEEK | PACK, PEEK | binding.GALV_DP_BP_U8, PEEK | PACK | binding.GALV_DP_STREAMS(3), PEEK | NO_PACK,
-                  NO_PACK | binding.GALV_DP_STREAMS(2)):
+                  NO_PACK | binding.GALV_DP_STREAMS(2), PEEK | PACK | WIDE, WIDE | binding.GALV_DP_BP_U8):
         check_against_oracle(w, flags=flags, table_instances=[1])
 
 

@@ -15,7 +15,9 @@ FLAGS = [0, binding.GALV_DP_NO_U32, binding.GALV_DP_FORCE_INT64, binding.GALV_DP
          binding.GALV_DP_BP_U8 | binding.GALV_DP_NO_U32, binding.GALV_DP_STREAMS(3),
          binding.GALV_DP_STREAMS(3) | binding.GALV_DP_BP_U8,
          binding.GALV_DP_FORCE_PEEK, binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_BP_U8 | binding.GALV_DP_STREAMS(2),
-         binding.GALV_DP_FORCE_PACK, binding.GALV_DP_FORCE_PACK | binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_STREAMS(2)]
+         binding.GALV_DP_FORCE_PACK, binding.GALV_DP_FORCE_PACK | binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_STREAMS(2),
+         binding.GALV_DP_FORCE_WIDE_TILES | binding.GALV_DP_FORCE_PACK | binding.GALV_DP_FORCE_PEEK,
+         binding.GALV_DP_FORCE_WIDE_TILES]
 
 
 @pytest.mark.parametrize("seed", [11, 12, 13])
@@ -23,7 +25,7 @@ def test_random_sweep(seed):
     rng = np.random.default_rng(seed)
     paths = set()
     for it in range(60):
-        S = int(rng.choice([1, 2, 3, 7, 8, 9, 11, 12, 16, 17, 22, 23, 31, 32, 33, 34, 43, 44, 45, 63, 64, 65,
+        S = int(rng.choice([1, 2, 3, 7, 8, 9, 11, 12, 16, 17, 18, 21, 22, 23, 31, 32, 33, 34, 40, 43, 44, 45, 63, 64, 65,
                             100, 127, 128, 129, 140]))
         L = int(rng.integers(1, 9))
         B = int(rng.integers(1, 5))

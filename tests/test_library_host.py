@@ -47,7 +47,7 @@ def test_bad_desc_is_invalid_arg(lib, args):
 
 def test_unknown_flag_and_range(lib):
     with pytest.raises(binding.GalvError) as ei:
-        binding.galv_dp_workspace_bytes(binding.make_desc(1, 4, 6, 256, 1, flags=0x80))
+        binding.galv_dp_workspace_bytes(binding.make_desc(1, 4, 6, 256, 1, flags=0x4000))
     assert ei.value.code == binding.GALV_ERR_INVALID_ARG
     with pytest.raises(binding.GalvError) as ei:
         binding.galv_dp_workspace_bytes(binding.make_desc(1, 4, 6, (1 << 30) + 1, 1))
