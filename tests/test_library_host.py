@@ -97,5 +97,5 @@ def test_one_byte_back_pointers_need_few_strategies(lib):
     bad = binding.make_desc(1, 4, 256, 256, flags=binding.GALV_DP_BP_U8)
     assert lib.galv_dp_workspace_bytes(ctypes.byref(bad), ctypes.byref(n)) == binding.GALV_ERR_INVALID_ARG
     assert "255" in binding.galv_dp_last_error()
-    unknown = binding.make_desc(1, 4, 6, 256, flags=0x80)
+    unknown = binding.make_desc(1, 4, 6, 256, flags=0x4000)
     assert lib.galv_dp_workspace_bytes(ctypes.byref(unknown), ctypes.byref(n)) == binding.GALV_ERR_INVALID_ARG
