@@ -103,7 +103,7 @@ typedef struct {
                                   enough workgroups to fill the chip (as for GALV_DP_FORCE_PEEK).
                                   Results, exported tables included, are identical either way.       */
 #define GALV_DP_FORCE_WIDE_TILES 128u   /* sweep workgroups take tiles of 256 budget columns instead of 128
-                                           (22, 44 and 128 strategies' kernel variants have such a twin).
+                                           (17 to 256 strategies: the kernel variants that have such a twin).
                                            By default this is done when a layer has enough workgroups to
                                            fill the chip, as for GALV_DP_FORCE_PEEK.  Results are identical. */
 #define GALV_DP_NO_WIDE_TILES 0x2000u   /* always 128-column tiles                                           */

@@ -1824,16 +1824,25 @@ __global__ __launch_bounds__(kThreads) void export_kernel(Layout a, int b, int64
 // for launches that fill the chip anyway: what a tile costs beside its min-plus arithmetic (its
 // chain of round trips, its addresses and bookkeeping) is spread over twice the states.
 // Measured against the 128-column variants: 3.5 % (44 strategies x 32768 columns x 64 instances),
-// 5 % (128 x 65536 x 16), 2 % (22 x 24576 x 32); 3 % slower on 22 x 16384 x 8, which does not fill
-// the chip and keeps the narrow tiles.
+// 5 % (128 x 65536 x 16), 2 % (22 x 24576 x 32), 3-6 % at 32, 64, 200 and 256 strategies; 3 %
+// slower on 22 x 16384 x 8, which does not fill the chip and keeps the narrow tiles.
 #ifndef GALV_V2X
 #define GALV_V2X 11, 2, 2, 5, 2, 2, 1
+#endif
+#ifndef GALV_V3X
+#define GALV_V3X 16, 2, 2, 4, 2, 2, 1
 #endif
 #ifndef GALV_V4X
 #define GALV_V4X 11, 2, 4, 5, 4, 2, 1
 #endif
+#ifndef GALV_V5X
+#define GALV_V5X 16, 2, 4, 4, 4, 2, 1
+#endif
 #ifndef GALV_V6X
 #define GALV_V6X 16, 2, 8, 4, 8, 2, 1
+#endif
+#ifndef GALV_V7X
+#define GALV_V7X 16, 2, 16, 4, 16, 2, 1
 #endif
 
 // ---------------------------------------------------------------------------------------------
@@ -1975,7 +1984,8 @@ const VariantEntry &pick_variant(int S, bool wide_tiles) {
         variant_entry<GALV_V3>(), variant_entry<GALV_V4>(), variant_entry<GALV_V5>(),
         variant_entry<GALV_V6>(), variant_entry<GALV_V7>(), variant_entry<GALV_V8>()};
     static const VariantEntry twins[] = {
-        variant_entry<GALV_V2X>(), variant_entry<GALV_V4X>(), variant_entry<GALV_V6X>()};
+        variant_entry<GALV_V2X>(), variant_entry<GALV_V3X>(), variant_entry<GALV_V4X>(),
+        variant_entry<GALV_V5X>(), variant_entry<GALV_V6X>(), variant_entry<GALV_V7X>()};
     constexpr int n = sizeof table / sizeof table[0];
     for (int i = 0; i < n; ++i)
         if (S <= table[i].v.ts * table[i].v.ng) {

@@ -301,7 +301,7 @@ def test_random_shapes_ragged_tiles(S):
                                   c_range=(0, 50), r_range=(0, 20), infeasible=0.08,
                                   zero_diagonal=False)
     w.budget[0] = E_max
-    WIDE = binding.GALV_DP_FORCE_WIDE_TILES        # 256-column tiles (variants of 22, 44, 128 strategies)
+    WIDE = binding.GALV_DP_FORCE_WIDE_TILES        # 256-column tiles (the variants for 17 to 256 strategies have such a twin)
     for flags in ALL_PATHS + (binding.GALV_DP_FORCE_PEEK, binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_FORCE_PACK,
                               WIDE | binding.GALV_DP_FORCE_PACK, WIDE | binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_FORCE_PACK,
                               WIDE | binding.GALV_DP_NO_PACK, WIDE | binding.GALV_DP_NO_U32):

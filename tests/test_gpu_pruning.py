@@ -19,7 +19,7 @@ pytestmark = pytest.mark.gpu
 
 PEEK, NO_PEEK = binding.GALV_DP_FORCE_PEEK, binding.GALV_DP_NO_PEEK
 NO_PACK = binding.GALV_DP_NO_PACK          # rolling cost rows + plain back-pointers
-WIDE = binding.GALV_DP_FORCE_WIDE_TILES    # 256-column tiles where the variant has such a twin (22, 44, 128 strategies)
+WIDE = binding.GALV_DP_FORCE_WIDE_TILES    # 256-column tiles where the variant has such a twin (17 to 256 strategies)
 PACK = binding.GALV_DP_FORCE_PACK          # the single packed table (these shapes are too small to choose it)
 
 
