@@ -1532,13 +1532,13 @@ __global__ __launch_bounds__(W * kWave, WPE) void sweep_kernel(Layout a, int l) 
         else
             sweep_u32<TS, TE * UX, NG, BP>(a, wave, l, b, budget, tile_start);
     } else if (st == GALV_INSTANCE_OK_U32_WIDE) {
-        // 8-byte cells: 64 columns at a time keep the rows within the registers the narrow form uses
-        // (the preparation kernel grants this path to row-sharing variants only)
+        // 8-byte cells: half the tile's columns at a time keep the rows within the registers the narrow
+        // form uses (the preparation kernel grants this path to row-sharing variants only)
         if constexpr (SHARE) {
-            for (int h = 0; h < TE * UX; ++h) {
-                if (tile_start + h * kWave > budget) break;          // workgroup-uniform
+            for (int h = 0; h < TE; ++h) {
+                if (tile_start + h * (kWave * UX) > budget) break;   // workgroup-uniform
                 if (h) __syncthreads();                              // the LDS of the part before is free again
-                sweep_u32_shared<TS, 1, NG, BP, uint64_t, PACK != 0, keep_rows(TS, NG, WPE, kWave * TE * UX)>(a, wave, l, b, budget, tile_start + h * kWave, h > 0, n_prev, dmax, r_sel, my_ent, my_c0);
+                sweep_u32_shared<TS, UX, NG, BP, uint64_t, PACK != 0, keep_rows(TS, NG, WPE, kWave * TE * UX)>(a, wave, l, b, budget, tile_start + h * (kWave * UX), h > 0, n_prev, dmax, r_sel, my_ent, my_c0);
             }
         }
     } else if (st == GALV_INSTANCE_OK_FAST) {
@@ -2079,8 +2079,9 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     if (v.share) {
         const size_t cols = (size_t)kWave * v.te * v.ux, keep = keep_rows(v.ts, v.ng, v.wpe, (int)cols);
         const size_t narrow = ((size_t)v.ng * cols + v.ng + 4 + keep + keep * cols) * sizeof(uint32_t);
-        // the 8-byte-cell form works on 64 columns at a time
-        const size_t wide = ((size_t)v.ng * kWave + v.ng) * sizeof(uint64_t) + (4 + keep + keep * kWave) * sizeof(uint32_t);
+        // the 8-byte-cell form works on a part of the tile (64 x ux columns) at a time
+        const size_t wcols = (size_t)kWave * v.ux;
+        const size_t wide = ((size_t)v.ng * wcols + v.ng) * sizeof(uint64_t) + (4 + keep + keep * wcols) * sizeof(uint32_t);
         p->lds_bytes = (unsigned)(narrow > wide ? narrow : wide);
     }
     if (p->lds_bytes > 160u * 1024u)
