@@ -1062,13 +1062,13 @@ __device__ __forceinline__ void sweep_u32(const Layout &a, int wave, int l, int 
 // How many surviving rows the row-sharing body below keeps in LDS for a workgroup that covers
 // `cap` strategies (host and device agree through this one function).
 // As many as the LDS holds without costing a resident workgroup: a CU holds wpe * 4 / ng
-// workgroups by registers, each may take that share of the 160 KB (at most the 64 KB a kernel
-// gets without asking); what the partial minima and counters leave goes to the list, in whole
-// rows per wave and pass.  8, 11, 16, 22, 32, 48, 96 and 96 rows for the eight variants below:
-// all rows up to 8 strategies, three quarters of them at 44 and 128.
+// workgroups by registers, each may take that share of the 160 KB (at most 128 KB); what the
+// partial minima and counters leave goes to the list, in whole rows per wave and pass.  With
+// 128-column tiles 8, 11, 16, 22, 32, 48, 96 and 224 rows for the eight variants below; with
+// 256-column tiles 12, 16, 24, 32, 64 and 96.
 constexpr int keep_rows(int ts, int ng, int wpe, int cols) {       // cols: budget columns of a tile
     const int wgs = wpe * 4 / ng > 0 ? wpe * 4 / ng : 1;
-    const int share = 160 * 1024 / wgs < 64 * 1024 ? 160 * 1024 / wgs : 64 * 1024;
+    const int share = 160 * 1024 / wgs < 128 * 1024 ? 160 * 1024 / wgs : 128 * 1024;
     const int fixed = ng * cols * 4 + ng * 8 + 16 + 256;
     int rows = (share - fixed) / (cols * 4 + 4);
     if (rows > ts * ng) rows = ts * ng;
