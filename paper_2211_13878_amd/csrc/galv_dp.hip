@@ -2285,6 +2285,16 @@ galv_status_t galv_dp_create(const galv_dp_desc_t *desc, void *workspace_dev,
     h->groups_y = p.groups_y;
     h->lds_bytes = p.lds_bytes;
     h->lds_allowed = p.lds_bytes <= 64u * 1024u;
+    if (!h->lds_allowed) {
+        // More than the default 64 KB of dynamic LDS: the kernel is told here, once, rather than at
+        // the first solve, which a caller may be capturing into a graph.  (Should this fail, the
+        // solve tries again and reports it.)
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(h->sweep), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)h->lds_bytes) == hipSuccess)
+            h->lds_allowed = true;
+        else
+            (void)hipGetLastError();
+    }
     h->solved = false;
     h->fresh = true;
     h->n_side = 0;

@@ -11,9 +11,14 @@ from paper_2211_13878_amd import binding, workloads
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("n_streams,extra", [(1, 0), (3, 0), (2, binding.GALV_DP_FORCE_PACK | binding.GALV_DP_FORCE_PEEK)])
-def test_capture_and_replay(n_streams, extra):
-    shapes = dict(B=6, L=10, S=40, E_max=1800)     # the variant that stages cells in LDS
+WIDE_PACKED = binding.GALV_DP_FORCE_PACK | binding.GALV_DP_FORCE_PEEK | binding.GALV_DP_FORCE_WIDE_TILES
+
+
+@pytest.mark.parametrize("n_streams,extra,S", [(1, 0, 40), (3, 0, 40),
+                                               (2, binding.GALV_DP_FORCE_PACK | binding.GALV_DP_FORCE_PEEK, 40),
+                                               (2, WIDE_PACKED, 100)])     # 256-column tiles: > 64 KB of LDS per workgroup
+def test_capture_and_replay(n_streams, extra, S):
+    shapes = dict(B=6, L=10 if S <= 64 else 6, S=S, E_max=1800 if S <= 64 else 900)
     ws = [workloads.random_workload(800 + i, shapes["B"], shapes["L"], shapes["S"], shapes["E_max"], nR=2,
                                     m_range=(0, 250), c_range=(0, 5000), r_range=(0, 900), infeasible=0.06)
           for i in range(4)]
