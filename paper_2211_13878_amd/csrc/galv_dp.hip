@@ -300,19 +300,29 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
     const int budget = uniform(a.budget[b]);
     if (tid == 0 && (budget < 0 || budget > a.E_max)) bad = 1;
 
-    // sum over layers of max_s c(l,s), saturating at 2^62
+    // sum over layers of max_s c(l,s), saturating at 2^62: a wave per layer, a lane per strategy
+    // (one thread walking a layer's strategies is a chain of loads, and with few layers most of
+    // the workgroup would idle)
+    const int wave = tid >> 6, lane = tid & 63;
     unsigned long long part = 0;
-    for (int64_t l = tid; l < L; l += kThreads) {
+    for (int64_t l = wave; l < L; l += kThreads / kWave) {
         unsigned long long mx = 0;
-        for (int64_t s = 0; s < S; ++s) {
+        for (int64_t s = lane; s < S; s += kWave) {
             const int64_t v = c[l * S + s];
             if (v < 0 || v >= kInf) bad = 1;
             if (m[l * S + s] < 0) bad = 1;
             if ((unsigned long long)v > mx) mx = (unsigned long long)v;
         }
-        if (ridx && l >= 1 && (ridx[l] < 0 || ridx[l] >= nR)) bad = 1;
-        part += mx;
-        if (part > cap) part = cap;
+#pragma unroll
+        for (int w = kWave / 2; w > 0; w >>= 1) {
+            const unsigned long long o = (unsigned long long)__shfl_xor((long long)mx, w, kWave);
+            if (o > mx) mx = o;
+        }
+        if (lane == 0) {
+            if (ridx && l >= 1 && (ridx[l] < 0 || ridx[l] >= nR)) bad = 1;
+            part += mx;
+            if (part > cap) part = cap;
+        }
     }
     red[tid] = part;
     __syncthreads();
@@ -350,14 +360,28 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
             }
             __syncthreads();
         }
-        if (tid == 0) {
-            for (int64_t l = 1; l < L; ++l) {
-                const int64_t k = ridx ? ridx[l] : 0;
-                if (k >= k0 && k < k0 + kn) {
-                    rsum += rmax[k - k0];
-                    if (rsum > cap) rsum = cap;
-                }
+        // (every thread adds up the layers it owns, saturating; one thread walking all layers is
+        // a chain of dependent loads that takes longer than the rest of this kernel)
+        unsigned long long part_r = 0;
+        for (int64_t l = 1 + tid; l < L; l += kThreads) {
+            const int64_t k = ridx ? ridx[l] : 0;
+            if (k >= k0 && k < k0 + kn) {
+                part_r += rmax[k - k0];
+                if (part_r > cap) part_r = cap;
             }
+        }
+        red[tid] = part_r;
+        __syncthreads();
+        for (int w = kThreads / 2; w > 0; w >>= 1) {
+            if (tid < w) {
+                const unsigned long long t = red[tid] + red[tid + w];      // each <= 2^62: no wrap
+                red[tid] = t > cap ? cap : t;
+            }
+            __syncthreads();
+        }
+        if (tid == 0) {
+            rsum += red[0];
+            if (rsum > cap) rsum = cap;
         }
         __syncthreads();
     }
@@ -443,26 +467,45 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
     // Per layer, the strategies whose memory fits the budget at all, in ascending
     // order, with their shift: the sweep of the next layer walks this list instead
     // of all S columns (a column that never fits is infinity everywhere).
-    for (int64_t l = tid; l < L; l += kThreads) {
+    // (a wave per layer, a lane per strategy: the usable ones find their place in the list by
+    // counting the usable lanes below them)
+    for (int64_t l = wave; l < L; l += kThreads / kWave) {
         uint64_t *lst = a.vlist + ((int64_t)b * L + l) * a.S_pad;
         uint64_t *lc = a.vcost + ((int64_t)b * L + l) * a.S_pad;
         int n = 0;
-        for (int s = 0; s < (int)S; ++s) {
-            const int sh = m[l * S + s];
-            if (sh <= budget) {
-                lc[n] = (uint64_t)c[l * S + s];
-                lst[n++] = ((uint64_t)(uint32_t)sh << 32) | (uint32_t)s;
+        uint64_t last_ent = 0, last_c = 0;         // the list's last entry so far (wave-uniform)
+        for (int s0 = 0; s0 < (int)S; s0 += kWave) {
+            const int sx = s0 + lane;
+            const bool in = sx < (int)S;
+            const int sh = in ? m[l * S + sx] : 0;
+            const uint64_t cv = in ? (uint64_t)c[l * S + sx] : 0;
+            const bool ok = in && sh <= budget;
+            const uint64_t ent = ((uint64_t)(uint32_t)sh << 32) | (uint32_t)sx;
+            const uint64_t votes = __builtin_amdgcn_ballot_w64(ok);
+            if (ok) {
+                const int pos = n + __builtin_popcountll(votes & ((1ull << lane) - 1ull));
+                lst[pos] = ent;
+                lc[pos] = cv;
+            }
+            if (votes != 0) {                      // wave-uniform
+                const int top = 63 - __builtin_clzll(votes);
+                last_ent = read_lane(ent, top);
+                last_c = read_lane(cv, top);
+                n += __builtin_popcountll(votes);
             }
         }
-        a.nvalid[(int64_t)b * L + l] = n;
-        if (l + 1 < L) a.hdr[((int64_t)b * L + l + 1) * 8 + 2] = n;
+        if (lane == 0) {
+            a.nvalid[(int64_t)b * L + l] = n;
+            if (l + 1 < L) a.hdr[((int64_t)b * L + l + 1) * 8 + 2] = n;
+        }
         // Past the list's end its last entry repeats (it changes no minimum: min(x, x) = x), so
         // a sweep that walks a fixed number of entries needs no bound check; an empty list is
         // never walked.
-        for (int i = n; i < a.S_pad && n > 0; ++i) {
-            lst[i] = lst[n - 1];
-            lc[i] = lc[n - 1];
-        }
+        if (n > 0)
+            for (int i = n + lane; i < a.S_pad; i += kWave) {
+                lst[i] = last_ent;
+                lc[i] = last_c;
+            }
     }
 }
 
