@@ -69,6 +69,8 @@ static __device__ __align__(256) unsigned char scratch[GALV_DP_STATIC_BYTES];
 namespace {
 
 constexpr int kThreads = 256;          // workgroup = 4 wavefronts of 64
+constexpr int kPrepThreads = 1024;     // prep_kernel: one workgroup per instance, whose loops are chains of
+                                       // load round trips: 16 wavefronts shorten each chain
 constexpr int kWave = 64;
 constexpr int kEAlign = 1024;          // budget columns are padded to this
 constexpr int kMaxS = 1024;
@@ -280,7 +282,7 @@ struct Wide {
 // One workgroup per instance.  Checks the value preconditions, bounds the
 // largest cost any plan prefix can reach, picks the arithmetic path and, for the
 // fast paths, packs R and c and lists the usable strategies of every layer.
-__global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags) {
+__global__ __launch_bounds__(kPrepThreads) void prep_kernel(Layout a, uint32_t flags) {
     const int b = blockIdx.x;
     const int tid = threadIdx.x;
     const int64_t L = a.L, S = a.S, nR = a.nR;
@@ -292,7 +294,7 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
 
     __shared__ int bad;
     __shared__ unsigned long long rmax[64];  // max of each transition matrix (64 at a time)
-    __shared__ unsigned long long red[kThreads];
+    __shared__ unsigned long long red[kPrepThreads];
     __shared__ unsigned long long bound_s;
     if (tid == 0) bad = 0;
     __syncthreads();
@@ -305,14 +307,17 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
     // the workgroup would idle)
     const int wave = tid >> 6, lane = tid & 63;
     unsigned long long part = 0;
-    for (int64_t l = wave; l < L; l += kThreads / kWave) {
+    for (int64_t l = wave; l < L; l += kPrepThreads / kWave) {
         unsigned long long mx = 0;
+        bool off = false;                          // (kept in a register: a store to `bad` inside the loop
+                                                   // would hold the next iteration's loads back)
+#pragma unroll 2
         for (int64_t s = lane; s < S; s += kWave) {
             const int64_t v = c[l * S + s];
-            if (v < 0 || v >= kInf) bad = 1;
-            if (m[l * S + s] < 0) bad = 1;
+            off |= v < 0 || v >= kInf || m[l * S + s] < 0;
             if ((unsigned long long)v > mx) mx = (unsigned long long)v;
         }
+        if (off) bad = 1;
 #pragma unroll
         for (int w = kWave / 2; w > 0; w >>= 1) {
             const unsigned long long o = (unsigned long long)__shfl_xor((long long)mx, w, kWave);
@@ -326,7 +331,7 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
     }
     red[tid] = part;
     __syncthreads();
-    for (int w = kThreads / 2; w > 0; w >>= 1) {
+    for (int w = kPrepThreads / 2; w > 0; w >>= 1) {
         if (tid < w) {
             const unsigned long long t = red[tid] + red[tid + w];
             red[tid] = t > cap ? cap : t;
@@ -343,14 +348,17 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
         for (int64_t k = 0; k < kn; ++k) {
             unsigned long long mx = 0;
             const int64_t *Rm = R + (k0 + k) * S * S;
-            for (int64_t i = tid; i < S * S; i += kThreads) {
+            bool off = false;
+#pragma unroll 4
+            for (int64_t i = tid; i < S * S; i += kPrepThreads) {
                 const int64_t v = Rm[i];
-                if (v < 0 || v >= kInf) bad = 1;
+                off |= v < 0 || v >= kInf;
                 if ((unsigned long long)v > mx) mx = (unsigned long long)v;
             }
+            if (off) bad = 1;
             red[tid] = mx;
             __syncthreads();
-            for (int w = kThreads / 2; w > 0; w >>= 1) {
+            for (int w = kPrepThreads / 2; w > 0; w >>= 1) {
                 if (tid < w && red[tid + w] > red[tid]) red[tid] = red[tid + w];
                 __syncthreads();
             }
@@ -363,7 +371,7 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
         // (every thread adds up the layers it owns, saturating; one thread walking all layers is
         // a chain of dependent loads that takes longer than the rest of this kernel)
         unsigned long long part_r = 0;
-        for (int64_t l = 1 + tid; l < L; l += kThreads) {
+        for (int64_t l = 1 + tid; l < L; l += kPrepThreads) {
             const int64_t k = ridx ? ridx[l] : 0;
             if (k >= k0 && k < k0 + kn) {
                 part_r += rmax[k - k0];
@@ -372,7 +380,7 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
         }
         red[tid] = part_r;
         __syncthreads();
-        for (int w = kThreads / 2; w > 0; w >>= 1) {
+        for (int w = kPrepThreads / 2; w > 0; w >>= 1) {
             if (tid < w) {
                 const unsigned long long t = red[tid] + red[tid + w];      // each <= 2^62: no wrap
                 red[tid] = t > cap ? cap : t;
@@ -420,7 +428,7 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
     // One record per layer with what a sweep workgroup needs before anything else, so that it
     // takes one load instead of a chain of them.  (The count of the former layer's usable
     // strategies is filled in below, by the thread that builds that layer's list.)
-    for (int64_t l = tid; l < L; l += kThreads) {
+    for (int64_t l = tid; l < L; l += kPrepThreads) {
         int32_t *h = a.hdr + ((int64_t)b * L + l) * 8;
         h[0] = st;
         h[1] = budget;
@@ -435,41 +443,41 @@ __global__ __launch_bounds__(kThreads) void prep_kernel(Layout a, uint32_t flags
     // that they never win and never read past the caller's matrix.
     const double scale = (double)(1ull << a.k_bits);
     double *Rk = a.Rk + (int64_t)b * nR * S * a.S_pad;
-    if (st == GALV_INSTANCE_OK_FAST_U32 || st == GALV_INSTANCE_OK_U32_WIDE) {
-        // 32-bit keys in the first half of each matrix's slot: rows of S_pad words, one matrix
-        // every S * S_pad doubles; padded columns hold the largest word.
-        for (int64_t i = tid; i < nR * S * a.S_pad; i += kThreads) {
-            const int64_t s = i % a.S_pad;
-            const int64_t sp = (i / a.S_pad) % S;
-            const int64_t k = i / (a.S_pad * S);
-            uint32_t *row = reinterpret_cast<uint32_t *>(Rk + k * S * a.S_pad) + sp * a.S_pad;
-            row[s] = (s < S) ? (((uint32_t)R[(k * S + sp) * S + s]) << a.k_bits) | (uint32_t)sp
-                             : 0xffffffffu;
-        }
-    } else {
-        for (int64_t i = tid; i < nR * S * a.S_pad; i += kThreads) {
-            const int64_t s = i % a.S_pad;
-            const int64_t sp = (i / a.S_pad) % S;
-            const int64_t k = i / (a.S_pad * S);
-            Rk[i] = (s < S) ? (double)R[(k * S + sp) * S + s] * scale + (double)sp : INFINITY;
+    // (a wave per matrix row / per layer and a lane per column: no index arithmetic per element)
+    constexpr int kWaves = kPrepThreads / kWave;
+    const int S_pad = a.S_pad;
+    const bool keys32 = st == GALV_INSTANCE_OK_FAST_U32 || st == GALV_INSTANCE_OK_U32_WIDE;
+    for (int64_t k = 0; k < nR; ++k) {
+        for (int sp = wave; sp < (int)S; sp += kWaves) {
+            const int64_t *src = R + (k * S + sp) * S;
+            if (keys32) {
+                // 32-bit keys in the first half of each matrix's slot: rows of S_pad words, one
+                // matrix every S * S_pad doubles; padded columns hold the largest word.
+                uint32_t *row = reinterpret_cast<uint32_t *>(Rk + k * S * S_pad) + (int64_t)sp * S_pad;
+                for (int sx = lane; sx < S_pad; sx += kWave)
+                    row[sx] = (sx < (int)S) ? (((uint32_t)src[sx]) << a.k_bits) | (uint32_t)sp : 0xffffffffu;
+            } else {
+                double *row = Rk + (k * S + sp) * S_pad;
+                for (int sx = lane; sx < S_pad; sx += kWave)
+                    row[sx] = (sx < (int)S) ? (double)src[sx] * scale + (double)sp : INFINITY;
+            }
         }
     }
     // c(l,s) in the form the epilogue adds: the integer itself (integer cells) or the
     // double c * 2^k (cells that hold 64-bit keys).
-    uint64_t *ck = a.ck + (int64_t)b * L * a.S_pad;
-    for (int64_t i = tid; i < L * a.S_pad; i += kThreads) {
-        const int64_t s = i % a.S_pad, l = i / a.S_pad;
-        const int64_t v = (s < S) ? c[l * S + s] : 0;
-        ck[i] = (narrow_cells(st) || st == GALV_INSTANCE_OK_U32_WIDE)
-                    ? (uint64_t)v
-                    : (uint64_t)__double_as_longlong((double)v * scale);
-    }
+    uint64_t *ck = a.ck + (int64_t)b * L * S_pad;
+    const bool c_int = narrow_cells(st) || st == GALV_INSTANCE_OK_U32_WIDE;
+    for (int64_t l = wave; l < L; l += kWaves)
+        for (int sx = lane; sx < S_pad; sx += kWave) {
+            const int64_t v = (sx < (int)S) ? c[l * S + sx] : 0;
+            ck[l * S_pad + sx] = c_int ? (uint64_t)v : (uint64_t)__double_as_longlong((double)v * scale);
+        }
     // Per layer, the strategies whose memory fits the budget at all, in ascending
     // order, with their shift: the sweep of the next layer walks this list instead
     // of all S columns (a column that never fits is infinity everywhere).
     // (a wave per layer, a lane per strategy: the usable ones find their place in the list by
     // counting the usable lanes below them)
-    for (int64_t l = wave; l < L; l += kThreads / kWave) {
+    for (int64_t l = wave; l < L; l += kPrepThreads / kWave) {
         uint64_t *lst = a.vlist + ((int64_t)b * L + l) * a.S_pad;
         uint64_t *lc = a.vcost + ((int64_t)b * L + l) * a.S_pad;
         int n = 0;
@@ -2219,7 +2227,7 @@ galv_status_t enqueue_solve(galv_dp *h, const int64_t *c_dev, const int32_t *m_d
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_bytes));
         h->lds_allowed = true;
     }
-    prep_kernel<<<a.B, kThreads, 0, st>>>(a, h->desc.flags);
+    prep_kernel<<<a.B, kPrepThreads, 0, st>>>(a, h->desc.flags);
     {
         // at most 16 cells per thread: enough blocks to write a row at full rate, few enough to cost
         // nothing when, as usual after a handle's first solve, there is nothing to write
