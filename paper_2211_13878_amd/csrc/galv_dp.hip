@@ -1177,6 +1177,10 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
     constexpr int kCols = kWave * TE;
     constexpr int kKeep = KEEP;                    // rows the list holds (keep_rows of the variant)
     (void)budget;
+    // A wave that has loads to issue goes before the waves that are in their arithmetic: the sooner a
+    // tile's requests are out, the shorter its chain of round trips, and the arithmetic of the other
+    // waves fills the time the requests take either way.  (Priority drops again before the inner loop.)
+    __builtin_amdgcn_s_setprio(3);
     const int lane = lane_id();                    // (g: the wave = owner of rows g + NG * r = strategy group)
     const int64_t e0 = tile_start + lane;
     const int64_t s0 = (int64_t)g * TS;
@@ -1425,6 +1429,7 @@ __device__ __forceinline__ void sweep_u32_shared(const Layout &a, int g, int l, 
     // was cleared while the pass before it was under way and after its last reader had gone.
     constexpr int kRpw = kKeep / NG;
     static_assert(kRpw >= 1, "one pass holds at least one row of every wave");
+    __builtin_amdgcn_s_setprio(0);                 // from here on arithmetic: let the waves that fetch go first
     int cnt = n > 0 ? uniform((int)count[0]) : 0;
     int r_next = TS;                               // first row of the next pass; TS: no further pass
     if (cnt > kKeep) {
