@@ -30,7 +30,9 @@
  *    so a solve may spread their layer sweeps over internal streams of the handle
  *    (forked from and joined back into `stream` with events; see GALV_DP_STREAMS),
  *    which lets sweeps of different instances overlap across layer boundaries.
- *    galv_dp_create touches no device memory (it may create those streams).
+ *    galv_dp_create touches no device memory (it may create those streams, and 64
+ *    bytes of pinned host memory through which a solve tells the next one how many
+ *    budget columns the batch really has).
  *  - Errors in host-visible arguments are returned as codes (never exceptions,
  *    never abort); galv_dp_last_error() gives a thread-local message.
  *  - Input VALUES live on the device and cannot be checked synchronously: a
@@ -108,7 +110,13 @@ typedef struct {
                                            fill the chip, as for GALV_DP_FORCE_PEEK.  Results are identical. */
 #define GALV_DP_NO_WIDE_TILES 0x2000u   /* always 128-column tiles                                           */
 #define GALV_DP_STREAMS_SHIFT 8 /* bits 8..12: how many internal streams the layer sweeps are   */
-#define GALV_DP_STREAMS_MASK 0x1f00u /* spread over; 0 = chosen from the shape, 1 = none, at most 16 */
+#define GALV_DP_STREAMS_MASK 0x1f00u /* spread over; 1 = none, at most 16; 0 = chosen by the library:
+                                        galv_dp_create makes as many as the shape could use with every
+                                        budget at max_budget, and each solve takes as many of them as
+                                        suit the budgets that the handle's PREVIOUS solve met (its
+                                        preparation kernel leaves their tile count in a word of
+                                        pinned host memory; no solve waits for it, and before the
+                                        first solve max_budget stands in).  Results never depend on it. */
 #define GALV_DP_STREAMS(n) ((uint32_t)(n) << GALV_DP_STREAMS_SHIFT)
 
 /* Per-instance status codes written by solve (see galv_dp_get_status). */
@@ -243,7 +251,8 @@ galv_status_t galv_dp_get_stats(galv_dp_t *h, int64_t *stats_dev, void *stream);
  * What galv_dp_create chose for this handle from the shape and the flags (host call, no GPU work):
  *   config [4] HOST int32  [0] 1 if 32-bit-key instances keep the single packed table (see
  *                              GALV_DP_FORCE_PACK), [1] 1 if the sweep peeks before it fetches a
- *                              row (GALV_DP_FORCE_PEEK), [2] internal streams, [3] budget columns
+ *                              row (GALV_DP_FORCE_PEEK), [2] internal streams the last solve used
+ *                              (before any solve: what the first will use), [3] budget columns
  *                              per sweep workgroup.
  * For benchmarks and tests that account for bytes moved; results never depend on any of it.
  */

@@ -150,6 +150,7 @@ struct Layout {
     int32_t *last;        // best last strategy  [B]
     int32_t *lead_mode;   // whose infinity leads the rows hold (lead_kind), 0 none  [B]
     uint32_t *stats;      // 32-bit-key sweeps, per tile: rows reduced << 16 | rows listed; rows fetched  [B][L-1][n_tiles][2]
+    int32_t *seen;        // pinned host word (or null): the budget tiles of all instances, as the last solve found them
     const int64_t *c;
     const int32_t *m;
     const int64_t *R;
@@ -301,6 +302,27 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(Layout a, uint32_t f
 
     const int budget = uniform(a.budget[b]);
     if (tid == 0 && (budget < 0 || budget > a.E_max)) bad = 1;
+
+    // What the batch's sweeps really cover: the budget tiles of all instances, told to the host (a
+    // word of pinned memory that the NEXT solve reads when it sizes its launches; the budgets live
+    // on the device, and a solve never waits for one).
+    if (a.seen && b == 0) {
+        unsigned long long tiles = 0;
+        for (int i = tid; i < a.B; i += kPrepThreads) {
+            const int e = a.budget[i];
+            if (e >= 0 && e <= a.E_max) tiles += (unsigned)(e / a.tile_e + 1);
+        }
+        red[tid] = tiles;
+        __syncthreads();
+        for (int w = kPrepThreads / 2; w > 0; w >>= 1) {
+            if (tid < w) red[tid] += red[tid + w];
+            __syncthreads();
+        }
+        if (tid == 0)
+            __hip_atomic_store(a.seen, (int32_t)(red[0] < 0x7fffffffull ? red[0] : 0x7fffffffull),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        __syncthreads();
+    }
 
     // sum over layers of max_s c(l,s), saturating at 2^62: a wave per layer, a lane per strategy
     // (one thread walking a layer's strategies is a chain of loads, and with few layers most of
@@ -2066,7 +2088,11 @@ struct galv_dp {
     bool lds_allowed;   // the kernel has been told that it may use that much
     bool solved;
     bool fresh;         // no solve has run over this workspace yet: the infinity leads are unwritten
-    int n_side;                    // > 1: the layer sweeps of disjoint instance ranges run on side streams
+    int n_side;                    // side streams the handle owns (0 or >= 2); a solve uses some or all of them
+    bool auto_streams;             // the solve picks how many (else: all of them, as the caller asked)
+    int n_used;                    // how many the last solve used (0: none has run)
+    int resident;                  // sweep workgroups the GPU holds at a time
+    int32_t *seen_host;            // pinned: budget tiles of the batch as the last solve's prep_kernel found them
     hipStream_t side[kMaxSide];
     hipEvent_t fork, join[kMaxSide];
 };
@@ -2156,6 +2182,7 @@ galv_status_t make_plan(const galv_dp_desc_t *d, Plan *p) {
     if ((d->flags & GALV_DP_FORCE_PACK) && v.share && !u8) packed = true;
     p->sweep = packed ? ve.fn_pack : (u8 ? ve.fn_u8 : ve.fn);
     a.packed = packed ? 1 : 0;
+    a.seen = nullptr;
     a.lead = (int64_t)round_up((size_t)a.E_max + 1, 64);
     a.row = a.lead + a.e_pad;
     p->var = v;
@@ -2213,6 +2240,31 @@ void bind_workspace(Layout &a, const Plan &p, char *ws) {
     a.stats = reinterpret_cast<uint32_t *>(ws + p.off_stats);
 }
 
+// How many internal streams a solve deals its instances over, given the budget tiles (sweep
+// workgroups per strategy group and layer) of the whole batch.  Measured on MI355X with 4 hardware
+// queues: the sweeps run fastest when one launch holds about two thirds of the workgroups the GPU
+// can keep resident, so that launches of different streams overlap in different phases (loads of
+// one under the arithmetic and stores of another) -- 64 instances of 44 strategies: 5-6 streams
+// for 4096 tiles, 6 for 5150, 9-10 for 8192, each 5-15 % ahead of two streams more or fewer; as
+// long as a launch still takes ~12 us (shorter ones are bound by the launch rate: 32 instances of
+// 22 strategies x 24576 columns take 1.16 / 1.20 / 1.70 ms with 2 / 3 / 4 streams).  A stream that
+// holds two instances where others hold one sets the pace, so when most streams would hold a
+// single instance every instance gets its own (16 instances of 128 strategies x 65536 columns:
+// 20.3 ms with 16 streams, 21.2 with 12, 22.1 with 11).
+int pick_streams(const galv_dp *h, int64_t tiles) {
+    if (h->n_side <= 1) return 1;
+    if (!h->auto_streams) return h->n_side;
+    const Layout &a = h->lay;
+    const double wgs = (double)tiles * h->groups_y;
+    int n = (int)(wgs / (0.66 * h->resident) + 0.5);
+    const double us = (double)tiles * a.tile_e * a.S * 8.0 / 5.5e12 * 1e6;   // a layer at 8 B per state
+    if (n > (int)(us / 12.0)) n = (int)(us / 12.0);
+    if (2 * n > a.B) n = a.B;
+    if (n > h->n_side) n = h->n_side;
+    return n < 1 ? 1 : n;
+}
+int64_t tiles_at_most(const galv_dp *h) { return (int64_t)h->lay.B * (h->lay.E_max / h->lay.tile_e + 1); }
+
 // Enqueue one whole solve (preparation, layer 0, the L-1 sweeps, final minimum) of handle h on
 // stream st.  Shared by every entry point that solves.
 galv_status_t enqueue_solve(galv_dp *h, const int64_t *c_dev, const int32_t *m_dev,
@@ -2241,7 +2293,12 @@ galv_status_t enqueue_solve(galv_dp *h, const int64_t *c_dev, const int32_t *m_d
     }
     a.b_off = 0;
     a.b_step = 1;
-    if (h->n_side <= 1 || a.L < 2) {
+    // (the budgets are on the device: what the last solve's preparation reported stands in for
+    // them, and the largest possible count before any has)
+    const int32_t seen = h->seen_host ? *static_cast<volatile int32_t *>(h->seen_host) : 0;
+    const int n_use = a.L < 2 ? 1 : pick_streams(h, seen > 0 ? seen : tiles_at_most(h));
+    h->n_used = n_use;
+    if (n_use <= 1) {
         const dim3 grid(kGridTiles(a.n_tiles), h->groups_y, a.B);
         for (int l = 1; l < a.L; ++l) h->sweep<<<grid, h->var.w * kWave, h->lds_bytes, st>>>(a, l);
     } else {
@@ -2252,14 +2309,14 @@ galv_status_t enqueue_solve(galv_dp *h, const int64_t *c_dev, const int32_t *m_d
         // A failure after the fork must not leave side streams running behind the caller's
         // back: whatever was started is still joined into `st` before the error is returned.
         hipError_t err = hipSuccess;
-        for (int g = 0; g < h->n_side && err == hipSuccess; ++g) {
-            const int count = (a.B - g + h->n_side - 1) / h->n_side;    // instances g, g + n, g + 2n, ...
+        for (int g = 0; g < n_use && err == hipSuccess; ++g) {
+            const int count = (a.B - g + n_use - 1) / n_use;            // instances g, g + n, g + 2n, ...
             if (count <= 0) continue;
             err = hipStreamWaitEvent(h->side[g], h->fork, 0);
             if (err != hipSuccess) break;                 // nothing enqueued on this side stream
             Layout ag = a;
             ag.b_off = g;
-            ag.b_step = h->n_side;
+            ag.b_step = n_use;
             const dim3 grid(kGridTiles(a.n_tiles), h->groups_y, count);
             for (int l = 1; l < a.L; ++l) h->sweep<<<grid, h->var.w * kWave, h->lds_bytes, h->side[g]>>>(ag, l);
             err = hipEventRecord(h->join[g], h->side[g]);
@@ -2354,22 +2411,41 @@ galv_status_t galv_dp_create(const galv_dp_desc_t *desc, void *workspace_dev,
     h->solved = false;
     h->fresh = true;
     h->n_side = 0;
+    h->n_used = 0;
+    h->seen_host = nullptr;
+    h->lay.seen = nullptr;
+    {
+        // workgroups of the sweep that the GPU holds at a time (by registers and LDS)
+        int per_cu = 0, cus = 0, dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+            cus = 256;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(h->sweep),
+                                                         h->var.w * kWave, h->lds_bytes) != hipSuccess || per_cu < 1)
+            per_cu = h->var.wpe * 4 / h->var.w > 0 ? h->var.wpe * 4 / h->var.w : 1;
+        (void)hipGetLastError();
+        h->resident = per_cu * cus;
+    }
     int n = (int)((desc->flags & GALV_DP_STREAMS_MASK) >> GALV_DP_STREAMS_SHIFT);
+    h->auto_streams = n == 0;
     if (n == 0) {
-        // Automatic, from the estimated duration of one layer's sweep when it streams 12 bytes
-        // per state at ~5.5 TB/s (within 2x of the measured single-stream launches of 11, 26, 105
-        // and 220 us on the four named shapes).  Measured on MI355X with 4 hardware queues:
-        // sweeps of 100 us and more gain 10-30 % from 8-10 streams (more than 10 lose again when
-        // a stream's launches get short: the launch rate binds) and still a few per cent when a
-        // launch takes a millisecond; sweeps of tens of microseconds gain ~10 % from 2 and lose
-        // with more; shorter ones lose with any.  A stream that holds two instances where
-        // others hold one sets the pace, so a batch of up to 16 large instances gets one
-        // stream per instance (16 instances of 128 strategies x 65536 columns: 22.1 ms with 16
-        // streams, 24.6 with 12, 25.3 with 9).
-        const double us = 12.0 * desc->n_instances * ((double)desc->max_budget + 1) *
-                          desc->n_strategies / 5.5e12 * 1e6;
-        n = us < 20.0 ? 1 : (us < 100.0 ? 2 : 9);
-        if (n == 9 && desc->n_instances <= kMaxSide && us / desc->n_instances >= 12.0) n = desc->n_instances;
+        // Automatic: the handle owns as many streams as its largest batch could use (pick_streams
+        // with every budget at the maximum), and every solve picks from the budgets the solve
+        // before it met.
+        h->n_side = kMaxSide;                      // (lets pick_streams answer for the cap below)
+        n = pick_streams(h, tiles_at_most(h));
+        h->n_side = 0;
+        if (n > 1 && hipHostMalloc(reinterpret_cast<void **>(&h->seen_host), 64, hipHostMallocDefault) == hipSuccess) {
+            *h->seen_host = 0;
+            void *dptr = nullptr;
+            if (hipHostGetDevicePointer(&dptr, h->seen_host, 0) == hipSuccess && dptr) {
+                h->lay.seen = static_cast<int32_t *>(dptr);
+            } else {
+                (void)hipHostFree(h->seen_host);
+                h->seen_host = nullptr;
+            }
+        }
+        (void)hipGetLastError();
     }
     if (n > desc->n_instances) n = desc->n_instances;
     if (n > 1 && desc->n_layers > 1) {
@@ -2387,6 +2463,7 @@ galv_status_t galv_dp_create(const galv_dp_desc_t *desc, void *workspace_dev,
             for (int g = 0; g < made_s; ++g) (void)hipStreamDestroy(h->side[g]);
             for (int g = 0; g < made_e; ++g) (void)hipEventDestroy(h->join[g]);
             if (have_fork) (void)hipEventDestroy(h->fork);
+            if (h->seen_host) (void)hipHostFree(h->seen_host);
             delete h;
             return fail(GALV_ERR_HIP, "creating internal streams failed: %s", hipGetErrorString(e));
         }
@@ -2452,7 +2529,12 @@ galv_status_t galv_dp_solve_static(const galv_dp_desc_t *desc, const int64_t *c_
     h.lds_allowed = p.lds_bytes <= 64u * 1024u;
     h.solved = false;
     h.fresh = true;            // the array keeps the last call's contents: write the leads anew
-    h.n_side = 0;
+    h.n_side = 0;              // the caller's stream only: nothing to create, nothing to adapt
+    h.auto_streams = false;
+    h.n_used = 0;
+    h.resident = 1;
+    h.seen_host = nullptr;
+    h.lay.seen = nullptr;
     bind_workspace(h.lay, p, static_cast<char *>(ws));
     hipStream_t st = static_cast<hipStream_t>(stream);
     rc = enqueue_solve(&h, c_dev, m_dev, R_dev, r_idx_dev, budget_dev, best_cost_dev, best_last_dev, st);
@@ -2530,7 +2612,7 @@ galv_status_t galv_dp_get_config(const galv_dp_t *h, int32_t *config) {
     if (!config) return fail(GALV_ERR_INVALID_ARG, "config is NULL");
     config[0] = h->lay.packed;
     config[1] = h->lay.peek && h->var.share ? 1 : 0;
-    config[2] = h->n_side > 1 ? h->n_side : 1;
+    config[2] = h->n_used > 0 ? h->n_used : (h->lay.L < 2 ? 1 : pick_streams(h, tiles_at_most(h)));
     config[3] = h->lay.tile_e;
     return GALV_OK;
 }
@@ -2609,6 +2691,7 @@ galv_status_t galv_dp_destroy(galv_dp_t *h) {
         }
         (void)hipEventDestroy(h->fork);
     }
+    if (h && h->seen_host) (void)hipHostFree(h->seen_host);
     delete h;
     return GALV_OK;
 }

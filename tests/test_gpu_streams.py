@@ -46,3 +46,32 @@ def test_too_many_streams_is_an_error():
     with pytest.raises(binding.GalvError) as e:
         binding.galv_dp_workspace_bytes(binding.make_desc(4, 4, 6, 256, flags=binding.GALV_DP_STREAMS(17)))
     assert e.value.code == binding.GALV_ERR_INVALID_ARG
+
+
+def test_automatic_stream_count_follows_the_budgets_the_last_solve_met():
+    """With no stream count asked for, a solve sizes its launches by the budget tiles the solve
+    before it found (the budgets live on the device; before any solve the largest possible count
+    stands in).  Whatever it picks, the results are the oracle's."""
+    import dataclasses
+    import numpy as np
+    B, L, S, E = 32, 3, 44, 16383
+    big = workloads.random_workload(910, B, L, S, E, m_range=(0, 2500), c_range=(0, 10 ** 5),
+                                    r_range=(0, 3 * 10 ** 4), infeasible=0.05)
+    big = dataclasses.replace(big, budget=np.full_like(big.budget, E))
+    small = dataclasses.replace(big, budget=np.full_like(big.budget, 1500))
+    sol = binding.Solver(B, L, S, E, 1, 0)
+    before = sol.config()["streams"]
+    assert before >= 2                      # a launch of this shape is worth splitting
+    used = []
+    for w in (big, small, small, big):
+        dev = binding.upload(w)
+        cost, _ = sol.solve(*dev)
+        plan = sol.backtrack()
+        cost, plan = cost.cpu().numpy(), plan.cpu().numpy()      # (waits for the solve)
+        used.append(sol.config()["streams"])
+        for b, ref in enumerate(oracle.solve_workload(w, threads=8)):
+            assert int(cost[b]) == ref.best_cost and (plan[b] == ref.plan).all(), (w is big, b)
+    sol.close()
+    # first solve: nothing seen yet; second: what the first met (the large budgets); third: the
+    # small budgets, a sixth of the columns, one launch per layer; fourth: still the small ones
+    assert used[0] == before and used[1] == before and used[2] == 1 and used[3] == 1, used
