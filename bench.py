@@ -71,7 +71,7 @@ BYTES_PER_STATE = {3: 4 + 4 + 4, 0: 4 + 4 + 4, 4: 8 + 8 + 4, 2: 8 + 8 + 4, 1: 8 
 # HBM bytes per sweep launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by the
 # same counter's reading for a 1 GiB copy: the `traffic_bytes_per_launch` line of
 # profiles/sweep_kernel_config<N>.md (tests/test_profiles.py keeps the two equal); None where not measured.
-MEASURED_TRAFFIC_BYTES = {3: 322258418, 4: 659495582}
+MEASURED_TRAFFIC_BYTES = {3: 322060786, 4: 659360817}
 
 
 def cpu_baseline(w):

@@ -2284,6 +2284,12 @@ galv_status_t enqueue_solve(galv_dp *h, const int64_t *c_dev, const int32_t *m_d
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_bytes));
         h->lds_allowed = true;
     }
+    // (the budgets are on the device: what an earlier solve's preparation reported stands in for
+    // them, and the largest possible count before any has; read before this solve's own
+    // preparation is launched, so that the choice does not depend on how fast that one runs)
+    const int32_t seen = h->seen_host ? *static_cast<volatile int32_t *>(h->seen_host) : 0;
+    const int n_use = a.L < 2 ? 1 : pick_streams(h, seen > 0 ? seen : tiles_at_most(h));
+    h->n_used = n_use;
     prep_kernel<<<a.B, kPrepThreads, 0, st>>>(a, h->desc.flags);
     {
         // at most 16 cells per thread: enough blocks to write a row at full rate, few enough to cost
@@ -2293,11 +2299,6 @@ galv_status_t enqueue_solve(galv_dp *h, const int64_t *c_dev, const int32_t *m_d
     }
     a.b_off = 0;
     a.b_step = 1;
-    // (the budgets are on the device: what the last solve's preparation reported stands in for
-    // them, and the largest possible count before any has)
-    const int32_t seen = h->seen_host ? *static_cast<volatile int32_t *>(h->seen_host) : 0;
-    const int n_use = a.L < 2 ? 1 : pick_streams(h, seen > 0 ? seen : tiles_at_most(h));
-    h->n_used = n_use;
     if (n_use <= 1) {
         const dim3 grid(kGridTiles(a.n_tiles), h->groups_y, a.B);
         for (int l = 1; l < a.L; ++l) h->sweep<<<grid, h->var.w * kWave, h->lds_bytes, st>>>(a, l);
