@@ -323,7 +323,10 @@ galv_status_t galv_dp_coarsen(int32_t n_instances, int32_t n_layers, int32_t n_s
 galv_status_t galv_dp_expand_plan(int32_t n_instances, int32_t n_layers, int32_t fuse,
                                   const int32_t *coarse_plan_dev, int32_t *plan_dev, void *stream);
 
-/* Free the handle (host memory only; the workspace stays the caller's). NULL is allowed. */
+/* Free the handle: its host memory, its internal streams and events, its word of pinned host memory
+ * (the workspace stays the caller's).  Call it once the streams given to this handle's solves have
+ * passed that work: a solve still in flight reads the handle's tables and writes that word.  NULL is
+ * allowed. */
 galv_status_t galv_dp_destroy(galv_dp_t *h);
 
 /* Message of the last error on this thread ("" if none). Never NULL. */
