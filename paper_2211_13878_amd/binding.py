@@ -329,7 +329,11 @@ class Solver:
         return dict(zip(("packed", "peek", "streams", "tile_columns"), galv_dp_get_config(self.handle)))
 
     def close(self):
+        """Waits for the device (a solve in flight still uses the handle's tables, streams and
+        pinned word), then frees the handle."""
         if self.handle is not None:
+            if torch.cuda.is_initialized():
+                torch.cuda.synchronize()
             galv_dp_destroy(self.handle)
             self.handle = None
 
