@@ -33,7 +33,8 @@ GALV_DP_NO_WIDE_TILES = 0x2000
 
 
 def GALV_DP_STREAMS(n: int) -> int:
-    """Flag bits asking for n internal streams (0 = automatic, 1 = none)."""
+    """Flag bits asking for n internal streams (1 = none; 0 = automatic: each solve then takes as
+    many as suit the budgets that the handle's previous solve met)."""
     return int(n) << 8
 
 GALV_INSTANCE_OK_FAST, GALV_INSTANCE_OK_INT64, GALV_INSTANCE_OK_FAST_WIDE, GALV_INSTANCE_OK_FAST_U32 = 0, 1, 2, 3
@@ -204,7 +205,8 @@ def galv_dp_get_stats(h, stats, stream=None):
 
 
 def galv_dp_get_config(h):
-    """(packed table, peek, internal streams, budget columns per workgroup) as the handle chose them."""
+    """(packed table, peek, internal streams the last solve used -- before any solve: what the first
+    will use --, budget columns per workgroup) as the handle chose them."""
     out = (ctypes.c_int32 * 4)()
     _check(load_library().galv_dp_get_config(h, out))
     return tuple(int(x) for x in out)
